@@ -1,0 +1,128 @@
+"""Pins for oracle/pack.py (CPU only)."""
+import heapq
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import pack as opk
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "pack_examples.txt")
+
+
+def _golden_cases():
+    out = []
+    for line in open(GOLD):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        parts = [[int(x) for x in p.split()] for p in line.split("|")]
+        out.append(tuple(parts))
+    return out
+
+
+@pytest.mark.parametrize("head,docs,assign,mb_len,mb_cost", _golden_cases())
+def test_hand_worked_examples(head, docs, assign, mb_len, mb_cost):
+    n, l_max, a, b = head
+    got = opk.pack(docs, n, l_max, a, b)
+    assert list(got[0]) == assign
+    assert list(got[1]) == mb_len
+    assert list(got[2]) == mb_cost
+
+
+def test_linear_cost_no_limit_is_lpt():
+    # with cost = length and no length limit the rule is Graham's longest-processing-time
+    # list scheduling; an independent heap formulation must give the same loads
+    rng = np.random.default_rng(7)
+    for trial in range(20):
+        docs = rng.integers(1, 500, size=40).tolist()
+        n = int(rng.integers(2, 7))
+        _, mb_len, mb_cost = opk.pack(docs, n, 10**9, 0, 1)
+        heap = [(0, j) for j in range(n)]
+        for d in sorted(docs, reverse=True):
+            load, j = heapq.heappop(heap)
+            heapq.heappush(heap, (load + d, j))
+        assert sorted(load for load, _ in heap) == sorted(mb_len)
+        assert mb_len == mb_cost
+        # LPT guarantee: makespan <= (4/3 - 1/(3N)) * optimum, optimum >= max(mean, longest)
+        lower = max(sum(docs) / n, max(docs))
+        assert max(mb_len) <= (4 / 3 - 1 / (3 * n)) * lower + max(docs)
+
+
+def _check_valid(docs, assign, mb_len, mb_cost, n, l_max, a, b):
+    assert len(assign) == len(docs)
+    for j in range(n):
+        members = [d for d, x in zip(docs, assign) if x == j]
+        assert sum(members) == mb_len[j] <= l_max
+        assert sum(a * d * d + b * d for d in members) == mb_cost[j]
+    assert all(-1 <= x < n for x in assign)
+
+
+def test_validity_and_leftover_rule():
+    rng = np.random.default_rng(11)
+    for trial in range(30):
+        docs = rng.integers(1, 300, size=60).tolist()
+        n, l_max, a, b = 4, 700, 3, 50
+        assign, mb_len, mb_cost = opk.pack(docs, n, l_max, a, b)
+        _check_valid(docs, assign, mb_len, mb_cost, n, l_max, a, b)
+        # replay: a document is left over only if even the fewest-token micro-batch is too full
+        order = sorted(range(len(docs)), key=lambda i: -docs[i])
+        lens = [0] * n
+        for i in order:
+            if assign[i] < 0:
+                assert min(lens) + docs[i] > l_max
+            else:
+                lens[assign[i]] += docs[i]
+
+
+def test_greedy_never_beats_bruteforce_optimum():
+    # Equation 2 (minimise the max micro-batch workload subject to the length cap)
+    rng = np.random.default_rng(5)
+    for trial in range(15):
+        docs = rng.integers(1, 30, size=7).tolist()
+        n, l_max, a, b = 3, 60, 2, 7
+        assign, mb_len, mb_cost = opk.pack(docs, n, l_max, a, b)
+        if min(assign) < 0:
+            continue
+        best = None
+        for x in itertools.product(range(n), repeat=len(docs)):
+            lens = [0] * n
+            cost = [0] * n
+            for d, j in zip(docs, x):
+                lens[j] += d
+                cost[j] += a * d * d + b * d
+            if max(lens) <= l_max:
+                best = max(cost) if best is None else min(best, max(cost))
+        assert best is not None and max(mb_cost) >= best
+        assert max(mb_cost) <= 2 * best      # list scheduling never exceeds twice the optimum
+
+
+def test_equal_lengths_keep_arrival_order():
+    docs = [5, 5, 5, 5]
+    assign, _, _ = opk.pack(docs, 2, 100, 1, 0)
+    assert assign == [0, 1, 0, 1]
+
+
+def test_stream_carries_leftovers_forward():
+    batches = [[10, 10, 9], [3, 2], [1]]
+    out, tail = opk.pack_stream(batches, 2, 10, 1, 0)
+    assert out[0][0] == [10, 10, 9] and out[0][1] == [0, 1, -1]
+    assert out[1][0][:1] == [9]                       # the left-over heads the next set
+    assert sorted(x for x in out[1][1]) == [0, 1, -1] or min(out[1][1]) >= 0
+    total_in = sum(sum(b) for b in batches)
+    total_packed = sum(sum(o[2]) for o in out)
+    assert total_in == total_packed + sum(tail)
+
+
+def test_fixed_arrival_packing():
+    seqs = opk.pack_fixed_arrival([5, 4, 7, 3], 8)
+    assert seqs == [[5, 3], [1, 7], [3]]
+    assert opk.imbalance([3, 1, 2]) == pytest.approx(1.5)
+
+
+def test_errors():
+    with pytest.raises(ValueError):
+        opk.pack([3, 0], 2, 10, 1, 1)
+    with pytest.raises(ValueError):
+        opk.pack([3], 0, 10, 1, 1)

@@ -1,0 +1,135 @@
+"""Pins for oracle/shard.py (CPU only)."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import shard as osh
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "shard_examples.txt")
+
+
+def _golden_cases():
+    out = []
+    for line in open(GOLD):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        head, docs, exp = [x.strip() for x in line.split("|")]
+        mode, cp, rank = head.split()
+        out.append((osh.PER_DOC_PADDED if mode == "per_doc" else osh.PER_SEQ, int(cp), int(rank),
+                    [int(x) for x in docs.split()], [int(x) for x in exp.split()]))
+    return out
+
+
+@pytest.mark.parametrize("mode,cp,rank,docs,exp", _golden_cases())
+def test_hand_worked_examples(mode, cp, rank, docs, exp):
+    r = osh.shard(docs, cp, rank, mode)
+    assert r["q_idx"].tolist() == exp
+
+
+def _rand_docs(rng, n, hi):
+    return rng.integers(1, hi, size=n, endpoint=True).tolist()
+
+
+@pytest.mark.parametrize("cp", [1, 2, 3, 4, 8])
+@pytest.mark.parametrize("mode", [osh.PER_DOC_PADDED, osh.PER_SEQ])
+def test_ranks_partition_the_sequence(cp, mode):
+    rng = np.random.default_rng(cp * 10 + mode)
+    docs = _rand_docs(rng, 13, 97)
+    total = sum(docs)
+    if mode == osh.PER_SEQ and total % (2 * cp):
+        docs[-1] += 2 * cp - total % (2 * cp)
+        total = sum(docs)
+    seen, sizes = [], set()
+    for r in range(cp):
+        out = osh.shard(docs, cp, r, mode)
+        q = out["q_idx"]
+        seen.extend(q[q >= 0].tolist())
+        sizes.add(len(q))
+        real = q[q >= 0]
+        assert (np.diff(real) > 0).all()           # strictly increasing real entries
+        assert out["cu_seqlens_q"][-1] == len(q)
+        assert out["cu_seqlens_k"].tolist() == np.concatenate([[0], np.cumsum(docs)]).tolist()
+    assert sorted(seen) == list(range(total))       # every token on exactly one rank
+    assert len(sizes) == 1                          # same number of slots on every rank
+    if mode == osh.PER_SEQ:
+        assert sizes.pop() == total // cp
+
+
+@pytest.mark.parametrize("cp", [2, 4, 8])
+def test_pair_count_closed_form_when_divisible(cp):
+    # chunk m of a document with chunk length c contributes m*c*c + c(c+1)/2 causal
+    # pairs, so the symmetric pair (r, 2CP-1-r) always gives (2CP-1)c^2 + c(c+1).
+    n = 2 * cp
+    docs = [n * c for c in (1, 3, 7, 20)]
+    want = sum((n - 1) * c * c + c * (c + 1) for c in (1, 3, 7, 20))
+    for r in range(cp):
+        assert osh.shard(docs, cp, r, osh.PER_DOC_PADDED)["useful_pairs"] == want
+    total_pairs = sum(L * (L + 1) // 2 for L in docs)
+    assert want * cp == total_pairs
+
+
+def test_useful_pairs_sum_to_total_with_padding():
+    docs = [5, 1, 17, 33, 2]
+    for cp in (2, 3, 4):
+        tot = sum(osh.shard(docs, cp, r, osh.PER_DOC_PADDED)["useful_pairs"] for r in range(cp))
+        assert tot == sum(L * (L + 1) // 2 for L in docs)
+
+
+def test_cp1_is_identity_without_padding():
+    docs = [3, 1, 7]
+    for mode in (osh.PER_DOC_PADDED, osh.PER_SEQ):
+        out = osh.shard(docs, 1, 0, mode)
+        assert out["q_idx"].tolist() == list(range(11))
+        assert out["cu_seqlens_q"].tolist() == [0, 3, 4, 11]
+        assert out["seg_k_begin"].tolist() == [0, 3, 4]
+        assert out["seg_k_end"].tolist() == [3, 4, 11]
+
+
+def test_single_divisible_document_same_in_both_modes():
+    for cp in (2, 4):
+        for r in range(cp):
+            a = osh.shard([8 * cp], cp, r, osh.PER_DOC_PADDED)
+            b = osh.shard([8 * cp], cp, r, osh.PER_SEQ)
+            for key in ("q_idx", "cu_seqlens_q", "seg_k_begin", "seg_k_end"):
+                assert a[key].tolist() == b[key].tolist()
+
+
+def test_segments_describe_the_rows():
+    docs = [5, 12, 1, 30]
+    for mode in (osh.PER_DOC_PADDED, osh.PER_SEQ):
+        dl = list(docs)
+        for r in range(2):
+            out = osh.shard(dl, 2, r, mode)
+            cu_k = out["cu_seqlens_k"]
+            for s in range(len(out["seg_k_begin"])):
+                rows = out["q_idx"][out["cu_seqlens_q"][s]:out["cu_seqlens_q"][s + 1]]
+                real = rows[rows >= 0]
+                kb, ke = out["seg_k_begin"][s], out["seg_k_end"][s]
+                assert kb in cu_k.tolist()
+                if len(real):
+                    d = np.searchsorted(cu_k, real, side="right") - 1
+                    assert (cu_k[d] == kb).all()          # one document per segment
+                    assert ke == real.max() + 1
+                else:
+                    assert ke == kb
+
+
+def test_per_sequence_is_imbalanced_per_document_is_not():
+    # a long document followed by short ones: the paper's motivating case (Section 3.1)
+    docs = [96] + [4] * 8
+    cp = 4
+    seq = [osh.shard(docs, cp, r, osh.PER_SEQ)["useful_pairs"] for r in range(cp)]
+    doc = [osh.shard(docs, cp, r, osh.PER_DOC_PADDED)["useful_pairs"] for r in range(cp)]
+    assert max(seq) / (sum(seq) / cp) > 1.2
+    assert max(doc) / (sum(doc) / cp) < 1.05
+
+
+def test_errors():
+    with pytest.raises(ValueError):
+        osh.shard([4, 0], 2, 0, osh.PER_DOC_PADDED)
+    with pytest.raises(ValueError):
+        osh.shard([4], 2, 2, osh.PER_DOC_PADDED)
+    with pytest.raises(ValueError):
+        osh.shard([5], 2, 0, osh.PER_SEQ)
