@@ -1,0 +1,190 @@
+/*
+ * wlb.h -- C ABI of the MI355X (gfx950) WLB-LLM hot path.
+ *
+ * Four groups of calls:
+ *   wlb_pack        workload-aware variable-length packing (host, integers)
+ *   wlb_shard*      context-parallel sharding maps          (host, integers)
+ *   wlb_attn_plan   tile schedule for the attention kernels (device, integers)
+ *   wlb_attn_fwd / wlb_attn_bwd   document-masked causal attention (device, bf16 MFMA)
+ *
+ * Conventions
+ *   - Every call returns a wlb_status; WLB_OK is 0.  No exception crosses the
+ *     boundary.  wlb_last_error() returns a thread-local, NUL-terminated text for
+ *     the last non-OK status returned on the calling thread.
+ *   - The caller owns every buffer.  "host" pointers are ordinary host memory;
+ *     "device" pointers are HIP device memory on the current device.  The library
+ *     keeps no device memory of its own: scratch lives in the caller's workspace,
+ *     sized by wlb_attn_workspace_size().
+ *   - Host calls are synchronous.  Device calls only enqueue work on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and return; they
+ *     never synchronise and never allocate.
+ *   - Token indices and offsets are int32 (T < 2^31); pair counts and costs are 64-bit.
+ *   - bf16 tensors are passed as void* to 2-byte elements, row-major, token-major:
+ *     Q, O, dO, dQ are [n_q][hq][head_dim]; K, V, dK, dV are [t_kv][hkv][head_dim];
+ *     LSE is float [hq][n_q].
+ */
+#ifndef WLB_H
+#define WLB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    WLB_OK = 0,
+    WLB_ERR_INVALID_ARG = 1,      /* null pointer, non-positive length, rank out of range, ... */
+    WLB_ERR_BUFFER_TOO_SMALL = 2, /* workspace smaller than wlb_attn_workspace_size() asks for */
+    WLB_ERR_UNSUPPORTED = 3,      /* head_dim other than 64 or 128, sizes beyond the int32 range */
+    WLB_ERR_HIP = 4               /* a HIP runtime call failed; text in wlb_last_error() */
+} wlb_status;
+
+const char* wlb_last_error(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Packing -- the greedy core of Algorithm 1 (paper Section 4.3), with the workload model of
+ * Equation 2 (Section 4.1): a micro-batch's workload is the sum over its documents of
+ * W_a(d) + W_l(d), attention quadratic and everything else linear in the document length
+ * (Sections 3.2 and 4.1):  cost(d) = cost_a*d*d + cost_b*d  in unsigned 64-bit integers.
+ *
+ * Documents are taken longest first (stable: equal lengths keep arrival order).  Each goes
+ * to the micro-batch with the least workload if its token count stays <= l_max, else to the
+ * micro-batch with the fewest tokens if it fits there, else it is left over (assign = -1)
+ * for the caller to carry into the next iteration.  Ties go to the lowest micro-batch index.
+ *
+ *   doc_len   host, [n_docs], each > 0
+ *   assign    host, [n_docs], out: micro-batch id in [0, n_microbatch) or -1
+ *   mb_len    host, [n_microbatch], out: tokens per micro-batch
+ *   mb_cost   host, [n_microbatch], out: workload per micro-batch
+ * Errors: INVALID_ARG for null pointers (n_docs == 0 is allowed), n_microbatch < 1,
+ * l_max < 1, a document length <= 0, or cost_a/cost_b so large that a full micro-batch
+ * (cost_a*l_max^2 + cost_b*l_max) would not fit in 64 bits.
+ */
+wlb_status wlb_pack(const int32_t* doc_len, int64_t n_docs,
+                    int32_t n_microbatch, int64_t l_max,
+                    uint64_t cost_a, uint64_t cost_b,
+                    int32_t* assign, int64_t* mb_len, uint64_t* mb_cost);
+
+/* ------------------------------------------------------------------------------------------
+ * Sharding maps (paper Section 3.1 for per-sequence, Section 5.1 for per-document).
+ *
+ * WLB_SHARD_PER_SEQ: the packed sequence is cut into 2*cp equal chunks; rank r owns chunks
+ * r and 2*cp-1-r.  Needs 2*cp | T.
+ * WLB_SHARD_PER_DOC_PADDED: every document is cut into 2*cp chunks of c = ceil(L/(2*cp))
+ * positions; rank r owns chunks r and 2*cp-1-r of every document; positions >= L are padding
+ * and appear as slots with q_idx = -1, so every rank has the same number of slots.
+ * cp == 1 is the identity map (no padding) in either mode.
+ *
+ * A rank's slots are ordered document-major, front chunk before back chunk.  A segment is a
+ * maximal run of slots from one chunk and one document.
+ *
+ * wlb_shard_size: host; writes the slot count n_q and segment count n_seg for `rank`.
+ * wlb_shard: host; all outputs are caller-allocated host arrays:
+ *   q_idx        [n_q]      global token index of each local slot, -1 = padding slot
+ *   cu_seqlens_q [n_seg+1]  slot offsets of the segments
+ *   seg_k_begin  [n_seg]    first key a segment's rows may see (= its document's start)
+ *   seg_k_end    [n_seg]    one past the last key the segment's last real row may see
+ *                           (= seg_k_begin when the segment has no real row)
+ *   cu_seqlens_k [n_docs+1] document offsets in the packed sequence
+ *   useful_pairs            this rank's count of in-document causal (query,key) pairs
+ * Any output pointer except q_idx may be NULL to skip it.
+ * Errors: INVALID_ARG for null doc_len/q_idx, n_docs < 1, cp < 1, rank outside [0,cp),
+ * unknown mode, a length <= 0, per-sequence mode with T not divisible by 2*cp;
+ * UNSUPPORTED when T (or the padded slot count) does not fit in int32.
+ */
+enum { WLB_SHARD_PER_DOC_PADDED = 0, WLB_SHARD_PER_SEQ = 1 };
+
+wlb_status wlb_shard_size(const int32_t* doc_len, int64_t n_docs, int32_t cp, int32_t rank,
+                          int32_t mode, int64_t* n_q, int64_t* n_seg);
+
+wlb_status wlb_shard(const int32_t* doc_len, int64_t n_docs, int32_t cp, int32_t rank, int32_t mode,
+                     int32_t* q_idx, int32_t* cu_seqlens_q, int32_t* seg_k_begin,
+                     int32_t* seg_k_end, int32_t* cu_seqlens_k, int64_t* useful_pairs);
+
+/* ------------------------------------------------------------------------------------------
+ * Attention on one context-parallel rank's rows (paper Sections 1 and 3.2 for the mask:
+ * a token attends only to earlier-or-equal tokens of its own document; Section 2.1 for the
+ * data flow: local Q rows against the gathered K/V of the whole packed sequence, K/V
+ * gradients leaving the rank as partial sums).
+ *
+ * The mask is defined per row from q_idx and cu_seqlens_k alone: a row whose global token
+ * index g lies in document [s, e) sees keys s..g inclusive.  Rows with q_idx = -1 are
+ * padding: their Q/dO content is ignored, O and dQ are written as 0, LSE as -inf, and they
+ * add nothing to dK/dV.  Softmax is over scale * <q, k>; LSE is the natural log of the sum
+ * of exponentials of the scaled scores.  Query head h uses KV head h / (hq/hkv).
+ */
+typedef struct {
+    int32_t n_q;       /* local query slots (rows of Q/O), >= 1                        */
+    int32_t t_kv;      /* tokens in the packed sequence (rows of K/V), >= 1           */
+    int32_t n_docs;    /* documents; cu_seqlens_k has n_docs+1 entries, last == t_kv  */
+    int32_t hq;        /* query heads                                                 */
+    int32_t hkv;       /* KV heads, hq % hkv == 0                                     */
+    int32_t head_dim;  /* 64 or 128                                                   */
+    float   scale;     /* softmax scale, finite and > 0                               */
+    int32_t flags;     /* WLB_ATTN_* bits                                             */
+} wlb_attn_desc;
+
+enum {
+    /* The workspace already holds the schedule that wlb_attn_plan (or an earlier
+     * wlb_attn_fwd/bwd without this flag) built for this same desc, q_idx and cu_seqlens_k:
+     * skip rebuilding it.  The mask is the same for every layer and for forward and
+     * backward, so one schedule serves them all. */
+    WLB_ATTN_REUSE_PLAN = 1
+};
+
+/* Bytes of device workspace needed (256-byte aligned pointer expected).  The forward needs
+ * fwd_bytes, the backward bwd_bytes >= fwd_bytes; the schedule sits at the start of the
+ * workspace in both, so one buffer of bwd_bytes serves plan, forward and backward. */
+wlb_status wlb_attn_workspace_size(const wlb_attn_desc* desc, size_t* fwd_bytes, size_t* bwd_bytes);
+
+/* Builds the tile schedule into the workspace (device, asynchronous): per-row key
+ * intervals, per-row-group key hulls and fully-visible ranges (so kernels skip cross-document
+ * tiles and mask only partial ones), the query-tile and key-tile work lists, both ordered
+ * longest first.  Called implicitly by wlb_attn_fwd / wlb_attn_bwd unless WLB_ATTN_REUSE_PLAN
+ * is set.  q_idx [n_q] and cu_seqlens_k [n_docs+1] are device pointers.
+ * Entries of q_idx must be -1 or in [0, t_kv); others are treated as padding. */
+wlb_status wlb_attn_plan(const wlb_attn_desc* desc, const int32_t* q_idx, const int32_t* cu_seqlens_k,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Where the schedule's arrays sit inside the workspace (byte offsets; for inspection and
+ * tests).  Row arrays have n_q entries; group arrays n_groups entries of 4 int32
+ * {k_lo, k_hi, max_lo, min_hi} per group of group_rows consecutive slots; the work lists are
+ * permutations of the query-tile / key-tile indices, heaviest first. */
+typedef struct {
+    int32_t group_rows, n_groups;
+    int32_t fwd_tile_rows, n_fwd_tiles;
+    int32_t bwd_key_tile, n_key_tiles;
+    size_t  off_row_lo, off_row_hi;      /* int32 [n_q]: visible keys are [lo, hi); pads: lo > hi */
+    size_t  off_group;                   /* int32 [n_groups][4] */
+    size_t  off_fwd_order;               /* int32 [n_fwd_tiles] */
+    size_t  off_fwd_cost;                /* int32 [n_fwd_tiles]: key tiles each query tile visits */
+    size_t  off_key_order;               /* int32 [n_key_tiles] */
+    size_t  off_key_range;               /* int32 [n_key_tiles][2]: first, one-past-last group that can see the tile */
+    size_t  plan_bytes;
+} wlb_plan_layout;
+
+wlb_status wlb_attn_plan_layout(const wlb_attn_desc* desc, wlb_plan_layout* layout);
+
+/* Forward.  Device pointers: q [n_q][hq][D], k, v [t_kv][hkv][D] (bf16), q_idx, cu_seqlens_k;
+ * outputs o [n_q][hq][D] bf16 and lse [hq][n_q] float are overwritten.
+ * Errors: INVALID_ARG (null pointer, bad desc), UNSUPPORTED (head_dim), BUFFER_TOO_SMALL,
+ * HIP (launch failure).  Nothing is launched when an error is returned. */
+wlb_status wlb_attn_fwd(const wlb_attn_desc* desc, const void* q, const void* k, const void* v,
+                        const int32_t* q_idx, const int32_t* cu_seqlens_k,
+                        void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward.  Takes the forward's o and lse plus d_o [n_q][hq][D]; overwrites dq [n_q][hq][D],
+ * dk and dv [t_kv][hkv][D] (bf16) with THIS call's rows' contribution (a CP rank's partial;
+ * keys no local row can see get 0).  Deterministic: no atomics. */
+wlb_status wlb_attn_bwd(const wlb_attn_desc* desc, const void* q, const void* k, const void* v,
+                        const void* o, const float* lse, const void* d_o,
+                        const int32_t* q_idx, const int32_t* cu_seqlens_k,
+                        void* dq, void* dk, void* dv,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WLB_H */

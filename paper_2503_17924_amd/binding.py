@@ -1,0 +1,237 @@
+"""ctypes binding of libwlb.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (see include/wlb.h).
+Host calls take and return numpy arrays; device calls take torch tensors that
+live on the GPU (torch is used for device memory and streams, nothing else) and
+enqueue work on torch's current stream.  There is no fallback: if the library
+is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libwlb.so")
+
+WLB_OK = 0
+SHARD_PER_DOC_PADDED = 0
+SHARD_PER_SEQ = 1
+ATTN_REUSE_PLAN = 1
+
+STATUS_NAMES = {0: "WLB_OK", 1: "WLB_ERR_INVALID_ARG", 2: "WLB_ERR_BUFFER_TOO_SMALL",
+                3: "WLB_ERR_UNSUPPORTED", 4: "WLB_ERR_HIP"}
+
+EXPORTS = ["wlb_last_error", "wlb_pack", "wlb_shard_size", "wlb_shard", "wlb_attn_workspace_size",
+           "wlb_attn_plan", "wlb_attn_plan_layout", "wlb_attn_fwd", "wlb_attn_bwd"]
+
+
+class WlbError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {text}")
+        self.status = status
+
+
+class AttnDesc(C.Structure):
+    _fields_ = [("n_q", C.c_int32), ("t_kv", C.c_int32), ("n_docs", C.c_int32), ("hq", C.c_int32),
+                ("hkv", C.c_int32), ("head_dim", C.c_int32), ("scale", C.c_float), ("flags", C.c_int32)]
+
+
+class PlanLayout(C.Structure):
+    _fields_ = [("group_rows", C.c_int32), ("n_groups", C.c_int32), ("fwd_tile_rows", C.c_int32),
+                ("n_fwd_tiles", C.c_int32), ("bwd_key_tile", C.c_int32), ("n_key_tiles", C.c_int32),
+                ("off_row_lo", C.c_size_t), ("off_row_hi", C.c_size_t), ("off_group", C.c_size_t),
+                ("off_fwd_order", C.c_size_t), ("off_fwd_cost", C.c_size_t), ("off_key_order", C.c_size_t),
+                ("off_key_range", C.c_size_t), ("plan_bytes", C.c_size_t)]
+
+
+_lib = None
+
+
+def lib():
+    """Loads libwlb.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2503_17924_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        L.wlb_last_error.restype = C.c_char_p
+        for name in EXPORTS[1:]:
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(st: int):
+    if st != WLB_OK:
+        raise WlbError(st, lib().wlb_last_error().decode())
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _np_ptr(a, ty):
+    return a.ctypes.data_as(C.POINTER(ty)) if a is not None else None
+
+
+# ------------------------------------------------------------------------------- host calls
+def wlb_pack(doc_len, n_microbatch: int, l_max: int, cost_a: int, cost_b: int):
+    """-> (assign int32[n_docs], mb_len int64[N], mb_cost uint64[N])"""
+    doc_len = _i32(doc_len)
+    n = int(doc_len.shape[0])
+    assign = np.empty(n, dtype=np.int32)
+    mb_len = np.empty(max(n_microbatch, 1), dtype=np.int64)
+    mb_cost = np.empty(max(n_microbatch, 1), dtype=np.uint64)
+    _check(lib().wlb_pack(_np_ptr(doc_len, C.c_int32), C.c_int64(n), C.c_int32(n_microbatch), C.c_int64(l_max),
+                          C.c_uint64(cost_a), C.c_uint64(cost_b), _np_ptr(assign, C.c_int32),
+                          _np_ptr(mb_len, C.c_int64), _np_ptr(mb_cost, C.c_uint64)))
+    return assign, mb_len[:n_microbatch], mb_cost[:n_microbatch]
+
+
+def wlb_shard_size(doc_len, cp: int, rank: int, mode: int):
+    doc_len = _i32(doc_len)
+    n_q, n_seg = C.c_int64(0), C.c_int64(0)
+    _check(lib().wlb_shard_size(_np_ptr(doc_len, C.c_int32), C.c_int64(doc_len.shape[0]), C.c_int32(cp),
+                                C.c_int32(rank), C.c_int32(mode), C.byref(n_q), C.byref(n_seg)))
+    return n_q.value, n_seg.value
+
+
+def wlb_shard(doc_len, cp: int, rank: int, mode: int):
+    """-> dict(q_idx, cu_seqlens_q, seg_k_begin, seg_k_end, cu_seqlens_k, useful_pairs)"""
+    doc_len = _i32(doc_len)
+    n_q, n_seg = wlb_shard_size(doc_len, cp, rank, mode)
+    n_docs = int(doc_len.shape[0])
+    q_idx = np.empty(n_q, dtype=np.int32)
+    cu_q = np.empty(n_seg + 1, dtype=np.int32)
+    kb = np.empty(n_seg, dtype=np.int32)
+    ke = np.empty(n_seg, dtype=np.int32)
+    cu_k = np.empty(n_docs + 1, dtype=np.int32)
+    pairs = C.c_int64(0)
+    _check(lib().wlb_shard(_np_ptr(doc_len, C.c_int32), C.c_int64(n_docs), C.c_int32(cp), C.c_int32(rank),
+                           C.c_int32(mode), _np_ptr(q_idx, C.c_int32), _np_ptr(cu_q, C.c_int32),
+                           _np_ptr(kb, C.c_int32), _np_ptr(ke, C.c_int32), _np_ptr(cu_k, C.c_int32),
+                           C.byref(pairs)))
+    return dict(q_idx=q_idx, cu_seqlens_q=cu_q, seg_k_begin=kb, seg_k_end=ke, cu_seqlens_k=cu_k,
+                useful_pairs=pairs.value)
+
+
+# ----------------------------------------------------------------------------- device calls
+def _desc(n_q, t_kv, n_docs, hq, hkv, head_dim, scale, flags=0):
+    return AttnDesc(int(n_q), int(t_kv), int(n_docs), int(hq), int(hkv), int(head_dim), float(scale), int(flags))
+
+
+def wlb_attn_workspace_size(desc: AttnDesc):
+    f, b = C.c_size_t(0), C.c_size_t(0)
+    _check(lib().wlb_attn_workspace_size(C.byref(desc), C.byref(f), C.byref(b)))
+    return f.value, b.value
+
+
+def wlb_attn_plan_layout(desc: AttnDesc) -> PlanLayout:
+    lay = PlanLayout()
+    _check(lib().wlb_attn_plan_layout(C.byref(desc), C.byref(lay)))
+    return lay
+
+
+def _dev_ptr(t, dtype=None):
+    import torch
+    if t is None:
+        return C.c_void_p(0)
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise TypeError("expected a contiguous GPU tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected dtype {dtype}, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def wlb_attn_plan(desc, q_idx, cu_seqlens_k, workspace):
+    import torch
+    _check(lib().wlb_attn_plan(C.byref(desc), _dev_ptr(q_idx, torch.int32), _dev_ptr(cu_seqlens_k, torch.int32),
+                               _dev_ptr(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
+                               _stream()))
+
+
+def wlb_attn_fwd(desc, q, k, v, q_idx, cu_seqlens_k, o, lse, workspace):
+    import torch
+    bf = torch.bfloat16
+    _check(lib().wlb_attn_fwd(C.byref(desc), _dev_ptr(q, bf), _dev_ptr(k, bf), _dev_ptr(v, bf),
+                              _dev_ptr(q_idx, torch.int32), _dev_ptr(cu_seqlens_k, torch.int32),
+                              _dev_ptr(o, bf), _dev_ptr(lse, torch.float32), _dev_ptr(workspace),
+                              C.c_size_t(workspace.numel() * workspace.element_size()), _stream()))
+
+
+def wlb_attn_bwd(desc, q, k, v, o, lse, d_o, q_idx, cu_seqlens_k, dq, dk, dv, workspace):
+    import torch
+    bf = torch.bfloat16
+    _check(lib().wlb_attn_bwd(C.byref(desc), _dev_ptr(q, bf), _dev_ptr(k, bf), _dev_ptr(v, bf), _dev_ptr(o, bf),
+                              _dev_ptr(lse, torch.float32), _dev_ptr(d_o, bf), _dev_ptr(q_idx, torch.int32),
+                              _dev_ptr(cu_seqlens_k, torch.int32), _dev_ptr(dq, bf), _dev_ptr(dk, bf),
+                              _dev_ptr(dv, bf), _dev_ptr(workspace),
+                              C.c_size_t(workspace.numel() * workspace.element_size()), _stream()))
+
+
+# ------------------------------------------------------------------ convenience (allocation only)
+class Attention:
+    """Owns the output tensors and workspace for one (shape, mask); all arithmetic is in libwlb."""
+
+    def __init__(self, q_idx, cu_seqlens_k, t_kv, hq, hkv, head_dim, scale, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.device = torch.device(device)
+        self.q_idx = torch.as_tensor(np.ascontiguousarray(q_idx, dtype=np.int32)).to(self.device)
+        self.cu_k = torch.as_tensor(np.ascontiguousarray(cu_seqlens_k, dtype=np.int32)).to(self.device)
+        self.n_q = int(self.q_idx.numel())
+        self.shape = (self.n_q, int(t_kv), int(self.cu_k.numel()) - 1, hq, hkv, head_dim, scale)
+        self.desc = _desc(*self.shape)
+        self.desc_reuse = _desc(*self.shape, flags=ATTN_REUSE_PLAN)
+        _, bwd_bytes = wlb_attn_workspace_size(self.desc)
+        self.workspace = torch.empty(bwd_bytes, dtype=torch.uint8, device=self.device)
+        self.planned = False
+
+    def plan(self):
+        wlb_attn_plan(self.desc, self.q_idx, self.cu_k, self.workspace)
+        self.planned = True
+
+    def forward(self, q, k, v, o=None, lse=None):
+        torch = self.torch
+        n_q, _, _, hq, _, d, _ = self.shape
+        if o is None:
+            o = torch.empty((n_q, hq, d), dtype=torch.bfloat16, device=self.device)
+        if lse is None:
+            lse = torch.empty((hq, n_q), dtype=torch.float32, device=self.device)
+        wlb_attn_fwd(self.desc_reuse if self.planned else self.desc, q, k, v, self.q_idx, self.cu_k, o, lse,
+                     self.workspace)
+        self.planned = True
+        return o, lse
+
+    def backward(self, q, k, v, o, lse, d_o, dq=None, dk=None, dv=None):
+        torch = self.torch
+        if dq is None:
+            dq = torch.empty_like(q)
+        if dk is None:
+            dk = torch.empty_like(k)
+        if dv is None:
+            dv = torch.empty_like(v)
+        wlb_attn_bwd(self.desc_reuse if self.planned else self.desc, q, k, v, o, lse, d_o, self.q_idx, self.cu_k,
+                     dq, dk, dv, self.workspace)
+        self.planned = True
+        return dq, dk, dv
+
+
+def bf16_bits_to_tensor(bits: np.ndarray, device="cuda:0"):
+    """numpy uint16 bf16 bit patterns -> torch.bfloat16 tensor on the device (a reinterpretation)."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device)
+    return t.view(torch.bfloat16)
+
+
+def tensor_to_f64(t) -> np.ndarray:
+    """GPU tensor (bf16 or fp32) -> numpy float64 on the host."""
+    return t.detach().to("cpu").double().numpy()

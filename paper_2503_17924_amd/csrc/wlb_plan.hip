@@ -1,0 +1,258 @@
+// Attention entry points of libwlb and the device-side tile scheduler.
+//
+// The scheduler turns (q_idx, cu_seqlens_k) into the integer tables the attention kernels
+// read: for every local row the interval [lo, hi) of keys it may see (its document's start up
+// to and including itself: causal inside the document, nothing outside -- paper Sections 1 and
+// 3.2); for every group of 64 consecutive rows the hull of those intervals and the range every
+// real row of the group sees in full; and two work lists ordered heaviest first -- query tiles
+// (forward and dQ) and key tiles (dK/dV).  Kernels visit only key tiles inside a hull and
+// apply the per-element mask only outside the fully visible range, which is how tiles that lie
+// wholly in other documents cost nothing (the tile-level waste described in Section 5.2).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+
+#include "wlb_device.h"
+#include "wlb_internal.h"
+
+namespace wlb {
+
+wlb_status check_desc(const wlb_attn_desc* d) {
+    if (!d) return fail(WLB_ERR_INVALID_ARG, "attention: null desc");
+    if (d->n_q < 1 || d->t_kv < 1 || d->n_docs < 1 || d->hq < 1 || d->hkv < 1)
+        return fail(WLB_ERR_INVALID_ARG, "attention: n_q=%d t_kv=%d n_docs=%d hq=%d hkv=%d", d->n_q, d->t_kv,
+                    d->n_docs, d->hq, d->hkv);
+    if (d->hq % d->hkv != 0) return fail(WLB_ERR_INVALID_ARG, "attention: hq=%d not a multiple of hkv=%d", d->hq, d->hkv);
+    if (!(d->scale > 0.0f) || !std::isfinite(d->scale)) return fail(WLB_ERR_INVALID_ARG, "attention: scale must be finite and > 0");
+    if (d->head_dim != 64 && d->head_dim != 128)
+        return fail(WLB_ERR_UNSUPPORTED, "attention: head_dim=%d (64 and 128 are built)", d->head_dim);
+    const int64_t qe = (int64_t)d->n_q * d->hq * d->head_dim, ke = (int64_t)d->t_kv * d->hkv * d->head_dim;
+    if (qe > 0x7fffffffLL * 8 || ke > 0x7fffffffLL * 8)
+        return fail(WLB_ERR_UNSUPPORTED, "attention: tensor too large");
+    if (d->flags & ~WLB_ATTN_REUSE_PLAN) return fail(WLB_ERR_INVALID_ARG, "attention: unknown flag bits 0x%x", d->flags);
+    return WLB_OK;
+}
+
+void plan_layout(const wlb_attn_desc& d, wlb_plan_layout* L) {
+    L->group_rows = kGroupRows;
+    L->n_groups = (d.n_q + kGroupRows - 1) / kGroupRows;
+    L->fwd_tile_rows = kFwdTileRows;
+    L->n_fwd_tiles = (d.n_q + kFwdTileRows - 1) / kFwdTileRows;
+    L->bwd_key_tile = kBwdKeyTile;
+    L->n_key_tiles = (d.t_kv + kBwdKeyTile - 1) / kBwdKeyTile;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    L->off_row_lo = take(sizeof(int32_t) * d.n_q);
+    L->off_row_hi = take(sizeof(int32_t) * d.n_q);
+    L->off_group = take(sizeof(int32_t) * 4 * L->n_groups);
+    L->off_fwd_order = take(sizeof(int32_t) * L->n_fwd_tiles);
+    L->off_fwd_cost = take(sizeof(int32_t) * L->n_fwd_tiles);
+    L->off_key_order = take(sizeof(int32_t) * L->n_key_tiles);
+    L->off_key_range = take(sizeof(int32_t) * 2 * L->n_key_tiles);
+    size_t key_cost = take(sizeof(int32_t) * L->n_key_tiles);   // scratch for the ordering
+    (void)key_cost;
+    L->plan_bytes = off;
+}
+
+static size_t off_key_cost(const wlb_plan_layout& L) {
+    return align_up(L.off_key_range + sizeof(int32_t) * 2 * L.n_key_tiles, 256);
+}
+
+// ------------------------------------------------------------------------------------------
+// kernels
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ int wave_min(int v) {
+    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ int wave_max(int v) {
+    for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ int wave_sum(int v) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// One wavefront per group of 64 rows: per-row [lo, hi) and the group's {k_lo, k_hi, max_lo, min_hi}.
+__global__ void __launch_bounds__(256) plan_rows_kernel(const int32_t* __restrict__ q_idx,
+                                                        const int32_t* __restrict__ cu, int n_q, int t_kv,
+                                                        int n_docs, int n_groups, int32_t* __restrict__ row_lo,
+                                                        int32_t* __restrict__ row_hi, int32_t* __restrict__ group) {
+    const int lane = threadIdx.x & 63;
+    const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (g >= n_groups) return;
+    const int i = g * kGroupRows + lane;
+    int lo = kPadLo, hi = 0;
+    if (i < n_q) {
+        const int tok = q_idx[i];
+        if (tok >= 0 && tok < t_kv) {
+            // last document start <= tok
+            int a = 0, b = n_docs;   // invariant: cu[a] <= tok < cu[b]
+            while (b - a > 1) {
+                const int m = (a + b) >> 1;
+                if (cu[m] <= tok) a = m; else b = m;
+            }
+            lo = cu[a];
+            hi = tok + 1;
+        }
+        row_lo[i] = lo;
+        row_hi[i] = hi;
+    }
+    const bool real = hi > 0;
+    const int k_lo = wave_min(lo);                       // pads carry INT_MAX
+    const int k_hi = wave_max(hi);                       // pads carry 0
+    const int max_lo = wave_max(real ? lo : 0);
+    const int min_hi = wave_min(real ? hi : kPadLo);
+    if (lane == 0) {
+        int4 out;
+        if (k_hi == 0) out = make_int4(0, 0, 0, 0);      // no real row in this group
+        else out = make_int4(k_lo, k_hi, max_lo, min_hi);
+        reinterpret_cast<int4*>(group)[g] = out;
+    }
+}
+
+// cost of a forward tile = number of 64-key tiles between the hull's ends
+__global__ void plan_fwd_cost_kernel(const int32_t* __restrict__ group, int n_groups, int n_tiles,
+                                     int groups_per_tile, int32_t* __restrict__ cost) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n_tiles) return;
+    int k_lo = kPadLo, k_hi = 0;
+    for (int j = 0; j < groups_per_tile; ++j) {
+        const int g = t * groups_per_tile + j;
+        if (g >= n_groups) break;
+        const int4 d = reinterpret_cast<const int4*>(group)[g];
+        if (d.y > d.x) { k_lo = min(k_lo, d.x); k_hi = max(k_hi, d.y); }
+    }
+    cost[t] = k_hi > k_lo ? (k_hi + 63) / 64 - k_lo / 64 : 0;
+}
+
+// One wavefront per key tile: which groups have a hull that touches it.
+__global__ void __launch_bounds__(256) plan_key_tiles_kernel(const int32_t* __restrict__ group, int n_groups,
+                                                             int n_key_tiles, int key_tile, int t_kv,
+                                                             int32_t* __restrict__ key_range,
+                                                             int32_t* __restrict__ key_cost) {
+    const int lane = threadIdx.x & 63;
+    const int kt = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (kt >= n_key_tiles) return;
+    const int k0 = kt * key_tile, k1 = min(k0 + key_tile, t_kv);
+    int first = kPadLo, last = 0, cnt = 0;
+    for (int g = lane; g < n_groups; g += 64) {
+        const int4 d = reinterpret_cast<const int4*>(group)[g];
+        if (d.y > d.x && d.x < k1 && d.y > k0) { first = min(first, g); last = max(last, g + 1); ++cnt; }
+    }
+    first = wave_min(first);
+    last = wave_max(last);
+    cnt = wave_sum(cnt);
+    if (lane == 0) {
+        key_range[2 * kt] = cnt ? first : 0;
+        key_range[2 * kt + 1] = cnt ? last : 0;
+        key_cost[kt] = cnt;
+    }
+}
+
+// order[rank] = index, heaviest first, ties by index (a counting rank; n is at most a few thousand)
+__global__ void plan_order_kernel(const int32_t* __restrict__ cost, int n, int32_t* __restrict__ order) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int c = cost[i];
+    int rank = 0;
+    for (int j = 0; j < n; ++j) {
+        const int cj = cost[j];
+        rank += (cj > c) || (cj == c && j < i);
+    }
+    order[rank] = i;
+}
+
+wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const int32_t* q_idx,
+                       const int32_t* cu_seqlens_k, char* ws, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    int32_t* row_lo = (int32_t*)(ws + L.off_row_lo);
+    int32_t* row_hi = (int32_t*)(ws + L.off_row_hi);
+    int32_t* group = (int32_t*)(ws + L.off_group);
+    int32_t* fwd_order = (int32_t*)(ws + L.off_fwd_order);
+    int32_t* fwd_cost = (int32_t*)(ws + L.off_fwd_cost);
+    int32_t* key_order = (int32_t*)(ws + L.off_key_order);
+    int32_t* key_range = (int32_t*)(ws + L.off_key_range);
+    int32_t* key_cost = (int32_t*)(ws + off_key_cost(L));
+    plan_rows_kernel<<<(L.n_groups + 3) / 4, 256, 0, stream>>>(q_idx, cu_seqlens_k, d.n_q, d.t_kv, d.n_docs,
+                                                                L.n_groups, row_lo, row_hi, group);
+    plan_fwd_cost_kernel<<<(L.n_fwd_tiles + 255) / 256, 256, 0, stream>>>(group, L.n_groups, L.n_fwd_tiles,
+                                                                          kFwdTileRows / kGroupRows, fwd_cost);
+    plan_key_tiles_kernel<<<(L.n_key_tiles + 3) / 4, 256, 0, stream>>>(group, L.n_groups, L.n_key_tiles,
+                                                                       kBwdKeyTile, d.t_kv, key_range, key_cost);
+    plan_order_kernel<<<(L.n_fwd_tiles + 255) / 256, 256, 0, stream>>>(fwd_cost, L.n_fwd_tiles, fwd_order);
+    plan_order_kernel<<<(L.n_key_tiles + 255) / 256, 256, 0, stream>>>(key_cost, L.n_key_tiles, key_order);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(WLB_ERR_HIP, "plan launch: %s", hipGetErrorString(e));
+    return WLB_OK;
+}
+
+static size_t delta_bytes(const wlb_attn_desc& d) { return align_up(sizeof(float) * (size_t)d.hq * d.n_q, 256); }
+
+}  // namespace wlb
+
+using namespace wlb;
+
+extern "C" wlb_status wlb_attn_workspace_size(const wlb_attn_desc* desc, size_t* fwd_bytes, size_t* bwd_bytes) {
+    if (wlb_status st = check_desc(desc)) return st;
+    if (!fwd_bytes || !bwd_bytes) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_workspace_size: null output");
+    wlb_plan_layout L;
+    plan_layout(*desc, &L);
+    *fwd_bytes = L.plan_bytes;
+    *bwd_bytes = L.plan_bytes + delta_bytes(*desc);
+    return WLB_OK;
+}
+
+extern "C" wlb_status wlb_attn_plan_layout(const wlb_attn_desc* desc, wlb_plan_layout* layout) {
+    if (wlb_status st = check_desc(desc)) return st;
+    if (!layout) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_plan_layout: null output");
+    plan_layout(*desc, layout);
+    return WLB_OK;
+}
+
+extern "C" wlb_status wlb_attn_plan(const wlb_attn_desc* desc, const int32_t* q_idx, const int32_t* cu_seqlens_k,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+    if (wlb_status st = check_desc(desc)) return st;
+    if (!q_idx || !cu_seqlens_k || !workspace) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_plan: null pointer");
+    wlb_plan_layout L;
+    plan_layout(*desc, &L);
+    if (workspace_bytes < L.plan_bytes)
+        return fail(WLB_ERR_BUFFER_TOO_SMALL, "wlb_attn_plan: workspace %zu < %zu bytes", workspace_bytes, L.plan_bytes);
+    return launch_plan(*desc, L, q_idx, cu_seqlens_k, (char*)workspace, stream);
+}
+
+extern "C" wlb_status wlb_attn_fwd(const wlb_attn_desc* desc, const void* q, const void* k, const void* v,
+                                   const int32_t* q_idx, const int32_t* cu_seqlens_k, void* o, float* lse,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+    if (wlb_status st = check_desc(desc)) return st;
+    if (!q || !k || !v || !o || !lse || !workspace) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_fwd: null pointer");
+    const bool reuse = desc->flags & WLB_ATTN_REUSE_PLAN;
+    if (!reuse && (!q_idx || !cu_seqlens_k)) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_fwd: null q_idx/cu_seqlens_k");
+    wlb_plan_layout L;
+    plan_layout(*desc, &L);
+    if (workspace_bytes < L.plan_bytes)
+        return fail(WLB_ERR_BUFFER_TOO_SMALL, "wlb_attn_fwd: workspace %zu < %zu bytes", workspace_bytes, L.plan_bytes);
+    if (!reuse)
+        if (wlb_status st = launch_plan(*desc, L, q_idx, cu_seqlens_k, (char*)workspace, stream)) return st;
+    return launch_fwd(*desc, L, q, k, v, o, lse, (char*)workspace, stream);
+}
+
+extern "C" wlb_status wlb_attn_bwd(const wlb_attn_desc* desc, const void* q, const void* k, const void* v,
+                                   const void* o, const float* lse, const void* d_o, const int32_t* q_idx,
+                                   const int32_t* cu_seqlens_k, void* dq, void* dk, void* dv, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+    if (wlb_status st = check_desc(desc)) return st;
+    if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !workspace)
+        return fail(WLB_ERR_INVALID_ARG, "wlb_attn_bwd: null pointer");
+    const bool reuse = desc->flags & WLB_ATTN_REUSE_PLAN;
+    if (!reuse && (!q_idx || !cu_seqlens_k)) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_bwd: null q_idx/cu_seqlens_k");
+    wlb_plan_layout L;
+    plan_layout(*desc, &L);
+    const size_t need = L.plan_bytes + delta_bytes(*desc);
+    if (workspace_bytes < need)
+        return fail(WLB_ERR_BUFFER_TOO_SMALL, "wlb_attn_bwd: workspace %zu < %zu bytes", workspace_bytes, need);
+    if (!reuse)
+        if (wlb_status st = launch_plan(*desc, L, q_idx, cu_seqlens_k, (char*)workspace, stream)) return st;
+    return launch_bwd(*desc, L, q, k, v, o, lse, d_o, dq, dk, dv, (char*)workspace, L.plan_bytes, stream);
+}

@@ -1,0 +1,133 @@
+"""CPU tests of the C-ABI library: it loads, exports every declared symbol, and its host
+entry points (wlb_pack, wlb_shard) are bit-exact against the oracle, including error paths."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import pack as opk
+from oracle import shard as osh
+from paper_2503_17924_amd import binding as B
+from paper_2503_17924_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "wlb.h")).read()
+    declared = set(re.findall(r"\b(wlb_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    L = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+@pytest.mark.parametrize("cp,mode", [(1, 0), (2, 0), (2, 1), (4, 0), (4, 1), (8, 0), (8, 1), (3, 0)])
+def test_shard_matches_oracle_random(cp, mode):
+    rng = np.random.default_rng(100 * cp + mode)
+    for trial in range(6):
+        docs = rng.integers(1, 200, size=int(rng.integers(1, 40))).astype(np.int32)
+        if mode == 1:
+            rem = int(docs.sum()) % (2 * cp)
+            if rem:
+                docs[-1] += 2 * cp - rem
+        for r in range(cp):
+            want = osh.shard(docs, cp, r, mode)
+            got = B.wlb_shard(docs, cp, r, mode)
+            for key in ("q_idx", "cu_seqlens_q", "seg_k_begin", "seg_k_end", "cu_seqlens_k"):
+                assert got[key].dtype == np.int32
+                assert got[key].tolist() == want[key].tolist(), key
+            assert got["useful_pairs"] == want["useful_pairs"]
+
+
+@pytest.mark.parametrize("cfg,cp,modes", [(0, 2, (0, 1)), (2, 8, (0, 1)), (4, 4, (0, 1)), (1, 1, (0,))])
+def test_shard_matches_oracle_on_benchmark_configs(cfg, cp, modes):
+    w = wl.config(cfg)
+    for mode in modes:
+        for r in sorted({0, cp - 1, cp // 2}):
+            want = osh.shard(w.doc_len, cp, r, mode)
+            got = B.wlb_shard(w.doc_len, cp, r, mode)
+            for key in ("q_idx", "cu_seqlens_q", "seg_k_begin", "seg_k_end", "cu_seqlens_k"):
+                assert np.array_equal(got[key], want[key]), key
+            assert got["useful_pairs"] == want["useful_pairs"]
+
+
+def test_shard_errors():
+    for args in (([4, 0], 2, 0, 0), ([4], 2, 2, 0), ([5], 2, 0, 1), ([4], 0, 0, 0), ([4], 2, 0, 7), ([4], 2, -1, 0)):
+        with pytest.raises(B.WlbError) as e:
+            B.wlb_shard(np.asarray(args[0], dtype=np.int32), *args[1:])
+        assert e.value.status == 1
+    with pytest.raises(B.WlbError) as e:
+        B.wlb_shard(np.full(3, 2**30, dtype=np.int32), 2, 0, 0)
+    assert e.value.status == 3
+
+
+def test_pack_matches_oracle_random():
+    rng = np.random.default_rng(42)
+    for trial in range(40):
+        n = int(rng.integers(0, 120))
+        docs = rng.integers(1, 5000, size=n).astype(np.int32)
+        nmb = int(rng.integers(1, 9))
+        l_max = int(rng.integers(4000, 40000))
+        a, b = int(rng.integers(0, 50)), int(rng.integers(0, 10**6))
+        want = opk.pack(docs, nmb, l_max, a, b)
+        got = B.wlb_pack(docs, nmb, l_max, a, b)
+        assert got[0].tolist() == list(want[0])
+        assert got[1].tolist() == list(want[1])
+        assert got[2].tolist() == list(want[2])
+
+
+def test_pack_matches_oracle_on_the_document_pool():
+    w = wl.config(3)
+    a, b = 6, 640000
+    want = opk.pack(w.doc_len, 8, 131072, a, b)
+    got = B.wlb_pack(w.doc_len, 8, 131072, a, b)
+    assert got[0].tolist() == list(want[0])
+    assert got[1].tolist() == list(want[1]) and got[2].tolist() == list(want[2])
+    # streamed as Algorithm 1's outer loop: global batches of 8 windows, left-overs carried over
+    seqs = opk.pack_fixed_arrival(w.doc_len, 131072)
+    batches = [sum(seqs[i:i + 8], []) for i in range(0, len(seqs), 8)]
+    remained = []
+    for cur in batches[:6]:
+        docs = np.asarray(remained + cur, dtype=np.int32)
+        want = opk.pack(docs, 8, 131072, a, b)
+        got = B.wlb_pack(docs, 8, 131072, a, b)
+        assert got[0].tolist() == list(want[0])
+        assert got[2].tolist() == list(want[2])
+        remained = [int(d) for d, j in zip(docs, want[0]) if j < 0]
+
+
+def test_pack_errors_and_limits():
+    d = np.asarray([3, 4], dtype=np.int32)
+    for args in ((d, 0, 10, 1, 1), (d, 2, 0, 1, 1), (np.asarray([3, 0], dtype=np.int32), 2, 10, 1, 1)):
+        with pytest.raises(B.WlbError) as e:
+            B.wlb_pack(*args)
+        assert e.value.status == 1
+    with pytest.raises(B.WlbError):
+        B.wlb_pack(d, 2, 2**40, 2**20, 0)           # a * l_max^2 overflows 64 bits
+    # largest admissible costs stay exact
+    got = B.wlb_pack(np.asarray([2**18], dtype=np.int32), 1, 2**18, 2**24, 2**40)
+    assert int(got[2][0]) == 2**24 * 2**36 + 2**40 * 2**18
+    # a document longer than l_max is left over
+    assert B.wlb_pack(np.asarray([11, 5], dtype=np.int32), 2, 10, 1, 0)[0].tolist() == [-1, 0]
+
+
+def test_attention_argument_checks_need_no_gpu():
+    d = B._desc(128, 128, 1, 4, 3, 128, 0.1)
+    with pytest.raises(B.WlbError) as e:
+        B.wlb_attn_workspace_size(d)
+    assert e.value.status == 1
+    d = B._desc(128, 128, 1, 4, 2, 96, 0.1)
+    with pytest.raises(B.WlbError) as e:
+        B.wlb_attn_workspace_size(d)
+    assert e.value.status == 3
+    d = B._desc(1000, 4096, 5, 8, 2, 128, 0.1)
+    f, b = B.wlb_attn_workspace_size(d)
+    lay = B.wlb_attn_plan_layout(d)
+    assert f == lay.plan_bytes and b >= f + 4 * 8 * 1000
+    assert lay.n_groups == 16 and lay.n_fwd_tiles == 8 and lay.n_key_tiles == 32
+    # null pointers are rejected before anything is launched
+    st = B.lib().wlb_attn_fwd(ctypes.byref(d), None, None, None, None, None, None, None, None, ctypes.c_size_t(0), None)
+    assert st == 1 and b"null" in B.lib().wlb_last_error()
