@@ -1,10 +1,438 @@
+// Backward document-masked attention for gfx950.  The paper measures forward+backward
+// latency of the attention kernel (Section 6.4) without restating the derivative; this is the
+// standard one: with P = exp(scale*Q K^T - LSE) on the visible (same-document, causal) pairs
+// and delta_i = <dO_i, O_i>,
+//     dV = P^T dO,  dP = dO V^T,  dS = P o (dP - delta),  dQ = scale * dS K,  dK = scale * dS^T Q,
+// dK/dV summed over the query heads that share a KV head.  As in all-gather context
+// parallelism (Section 2.1) dK/dV hold only the calling rank's rows' contribution.
+//
+// Three kernels, no atomics, deterministic:
+//   delta_kernel  delta[h][i] = sum_d dO*O (0 for padding rows)
+//   dq_kernel     query-stationary, same tiling as the forward: S^T and dP^T per lane column,
+//                 dQ^T += K^T dS^T with K^T read from LDS by transpose reads
+//   dkv_kernel    key-stationary: a workgroup owns 128 keys of one KV head (32 per wavefront,
+//                 their K and V MFMA operands live in registers), streams the row groups that
+//                 can see them through LDS for every query head of the KV group, and keeps
+//                 dK^T, dV^T in registers until the single final store.
+// Q / dO / K tiles that are read both row-wise (b128) and column-wise (transpose reads) are
+// stored unpadded with an XOR swizzle of their 16-byte chunks that makes both patterns
+// bank-conflict free.
 #include <hip/hip_runtime.h>
+
 #include "wlb_device.h"
 #include "wlb_internal.h"
+
 namespace wlb {
+
+// physical 16-byte chunk of logical chunk `cc` in row `r` (CPR chunks per row)
+template <int CPR>
+__device__ __forceinline__ int swz(int r, int cc) {
+    return cc ^ ((((r & 3) << 2) | ((r >> 2) & 3)) & (CPR - 1));
+}
+
+struct BwdParams {
+    const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* o; const __bf16* d_o;
+    const float* lse; float* delta;
+    __bf16* dq; __bf16* dk; __bf16* dv;
+    const int32_t* row_lo; const int32_t* row_hi; const int32_t* group;
+    const int32_t* fwd_order; const int32_t* key_order; const int32_t* key_range;
+    int n_q, t_kv, hq, hkv, n_groups, n_tiles, n_key_tiles;
+    float scale_log2e, scale;
+};
+
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(256) delta_kernel(const BwdParams p) {
+    constexpr int LPR = D / 8;                       // lanes per (row, head)
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t rh = idx / LPR;                     // row * hq + head
+    const int c = (int)(idx % LPR);
+    const size_t total = (size_t)p.n_q * p.hq;
+    float acc = 0.f;
+    if (rh < total) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(p.d_o + rh * D + c * 8);
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(p.o + rh * D + c * 8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc += (float)a[i] * (float)b[i];
+    }
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    if (rh < total && c == 0) {
+        const int row = (int)(rh / p.hq), h = (int)(rh % p.hq);
+        p.delta[(size_t)h * p.n_q + row] = p.row_hi[row] > 0 ? acc : 0.f;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// dQ: one workgroup = 128 query rows x one head; wavefront = QB blocks of 32 rows.
+template <int D, int QB, int NW>
+__global__ void __launch_bounds__(NW * 64) dq_kernel(const BwdParams p) {
+    constexpr int BM = 32 * QB * NW;
+    static_assert(BM == kFwdTileRows, "tile rows must match the schedule");
+    constexpr int BN = 64, NT = NW * 64, KS = D / 16, DB = D / 32, CPR = D / 8;
+    constexpr int VSTR = D + 8;
+
+    __shared__ __attribute__((aligned(16))) __bf16 Ks[BN * D];       // swizzled
+    __shared__ __attribute__((aligned(16))) __bf16 Vs[BN * VSTR];    // padded, row reads only
+
+    const int G = p.hq / p.hkv;
+    const int x = blockIdx.x & 7;
+    int y = blockIdx.x >> 3;
+    const int hh = y % G; y /= G;
+    const int hk = y % p.hkv;
+    const int c = y / p.hkv;
+    const int rank = c * 8 + x;
+    if (rank >= p.n_tiles) return;
+    const int tile = p.fwd_order[rank];
+    const int h = hk * G + hh;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    int k_lo = kPadLo, k_hi = 0, max_lo = 0, min_hi = kPadLo;
+    for (int j = 0; j < BM / kGroupRows; ++j) {
+        const int g = tile * (BM / kGroupRows) + j;
+        if (g < p.n_groups) {
+            const int4 d = reinterpret_cast<const int4*>(p.group)[g];
+            if (d.y > d.x) { k_lo = min(k_lo, d.x); k_hi = max(k_hi, d.y); max_lo = max(max_lo, d.z); min_hi = min(min_hi, d.w); }
+        }
+    }
+    int jb = 0, je = 0, fb = 0, fe = 0;
+    if (k_hi > k_lo) {
+        jb = k_lo / BN; je = (k_hi + BN - 1) / BN;
+        fb = (max_lo + BN - 1) / BN; fe = min_hi / BN;
+        if (fe < fb) fe = fb;
+    }
+
+    bf16x8 qf[QB][KS], dof[QB][KS];
+    int lo[QB], hi[QB], row[QB];
+    float lsec[QB], dl[QB];
+#pragma unroll
+    for (int b = 0; b < QB; ++b) {
+        row[b] = tile * BM + (wave * QB + b) * 32 + l32;
+        const bool in = row[b] < p.n_q;
+        const int rc = in ? row[b] : p.n_q - 1;
+        lo[b] = in ? p.row_lo[rc] : kPadLo;
+        hi[b] = in ? p.row_hi[rc] : 0;
+        const bool real = hi[b] > 0;
+        // padding rows: zero operands and LSE = +inf make P, dS and dQ exactly 0
+        lsec[b] = real ? p.lse[(size_t)h * p.n_q + rc] * 1.4426950408889634f : INFINITY;
+        dl[b] = real ? p.delta[(size_t)h * p.n_q + rc] : 0.f;
+        const __bf16* qp = p.q + ((size_t)rc * p.hq + h) * D + half * 8;
+        const __bf16* dp = p.d_o + ((size_t)rc * p.hq + h) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 a = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+            bf16x8 g = *reinterpret_cast<const bf16x8*>(dp + ks * 16);
+            if (!real) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { a[i] = (__bf16)0.f; g[i] = (__bf16)0.f; }
+            }
+            qf[b][ks] = a; dof[b][ks] = g;
+        }
+    }
+
+    f32x16 acc[QB][DB];
+#pragma unroll
+    for (int b = 0; b < QB; ++b)
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[b][db][r] = 0.f;
+
+    const float cs = p.scale_log2e;
+    const size_t kv_row = (size_t)p.hkv * D;
+    const __bf16* kbase = p.k + (size_t)hk * D;
+    const __bf16* vbase = p.v + (size_t)hk * D;
+    const int j16 = lane & 15, gi = (lane >> 4) & 1;
+
+    for (int j = jb; j < je; ++j) {
+        __syncthreads();
+        for (int ch = tid; ch < BN * CPR; ch += NT) {
+            const int r = ch / CPR, cc = ch % CPR;
+            const int kr = min(j * BN + r, p.t_kv - 1);
+            const i32x4 kk = *reinterpret_cast<const i32x4*>(kbase + (size_t)kr * kv_row + cc * 8);
+            const i32x4 vv = *reinterpret_cast<const i32x4*>(vbase + (size_t)kr * kv_row + cc * 8);
+            *reinterpret_cast<i32x4*>(&Ks[r * D + swz<CPR>(r, cc) * 8]) = kk;
+            *reinterpret_cast<i32x4*>(&Vs[r * VSTR + cc * 8]) = vv;
+        }
+        __syncthreads();
+        const bool partial = (j < fb) || (j >= fe);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            f32x16 s[QB], dp[QB];
+#pragma unroll
+            for (int b = 0; b < QB; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { s[b][r] = 0.f; dp[b][r] = 0.f; }
+            const int kr = kb * 32 + l32;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8 ka = *reinterpret_cast<const bf16x8*>(&Ks[kr * D + swz<CPR>(kr, ks * 2 + half) * 8]);
+                const bf16x8 va = *reinterpret_cast<const bf16x8*>(&Vs[kr * VSTR + ks * 16 + half * 8]);
+#pragma unroll
+                for (int b = 0; b < QB; ++b) {
+                    s[b] = mfma32(ka, qf[b][ks], s[b]);
+                    dp[b] = mfma32(va, dof[b][ks], dp[b]);
+                }
+            }
+            bf16x8 dsf[QB][2];
+#pragma unroll
+            for (int b = 0; b < QB; ++b) {
+                float ds[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float pr = fast_exp2(fmaf(s[b][r], cs, -lsec[b]));
+                    if (partial) {
+                        const int key = j * BN + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                        pr = (key >= lo[b] && key < hi[b]) ? pr : 0.f;
+                    }
+                    ds[r] = pr * (dp[b][r] - dl[b]);
+                }
+                dsf[b][0] = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
+                dsf[b][1] = pack8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
+            }
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+                const int key0 = kb * 32 + cc * 16 + half * 4 + (j16 >> 2);
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);       // logical 16-byte chunk
+                    const int dsub = (j16 & 1) * 4;                            // element offset inside it
+                    const bf16x4 k0v = lds_read_tr4(&Ks[key0 * D + swz<CPR>(key0, dch) * 8 + dsub]);
+                    const bf16x4 k1v = lds_read_tr4(&Ks[(key0 + 8) * D + swz<CPR>(key0 + 8, dch) * 8 + dsub]);
+                    const bf16x8 a = cat4(k0v, k1v);
+#pragma unroll
+                    for (int b = 0; b < QB; ++b) acc[b][db] = mfma32(a, dsf[b][cc], acc[b][db]);
+                }
+            }
+        }
+    }
+
+#pragma unroll
+    for (int b = 0; b < QB; ++b) {
+        if (row[b] < p.n_q) {
+            const bool real = hi[b] > 0;
+            __bf16* op = p.dq + ((size_t)row[b] * p.hq + h) * D;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int d = db * 32 + r4 * 8 + half * 4;
+                    bf16x4 out;
+                    if (real) out = pack4(acc[b][db][r4 * 4 + 0] * p.scale, acc[b][db][r4 * 4 + 1] * p.scale,
+                                          acc[b][db][r4 * 4 + 2] * p.scale, acc[b][db][r4 * 4 + 3] * p.scale);
+                    else out = pack4(0.f, 0.f, 0.f, 0.f);
+                    *reinterpret_cast<bf16x4*>(op + d) = out;
+                }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// dK/dV: one workgroup = 128 keys x one KV head; wavefront w owns keys [k0+32w, k0+32w+32).
+template <int D>
+__global__ void __launch_bounds__(256) dkv_kernel(const BwdParams p) {
+    constexpr int BNK = kBwdKeyTile, GR = kGroupRows, KS = D / 16, DB = D / 32, CPR = D / 8;
+    static_assert(BNK == 128 && GR == 64, "tiling");
+
+    __shared__ __attribute__((aligned(16))) __bf16 Qs[GR * D];     // swizzled
+    __shared__ __attribute__((aligned(16))) __bf16 Os[GR * D];     // dO, swizzled
+    __shared__ __attribute__((aligned(16))) float lse_s[GR];       // LSE * log2(e); +inf for padding rows
+    __shared__ __attribute__((aligned(16))) float dl_s[GR];
+    __shared__ __attribute__((aligned(16))) int lo_s[GR];
+    __shared__ __attribute__((aligned(16))) int hi_s[GR];
+
+    const int G = p.hq / p.hkv;
+    const int x = blockIdx.x & 7;
+    const int y = blockIdx.x >> 3;
+    const int hk = y % p.hkv;
+    const int c = y / p.hkv;
+    const int rank = c * 8 + x;
+    if (rank >= p.n_key_tiles) return;
+    const int kt = p.key_order[rank];
+    const int k0 = kt * BNK;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int j16 = lane & 15, gi = (lane >> 4) & 1;
+    const int kw0 = k0 + wave * 32;            // this wavefront's first key
+    const int mykey = kw0 + l32;
+
+    // K and V operands of this wavefront's 32 keys (B operands: column = key, 8 consecutive d)
+    bf16x8 kf[KS], vf[KS];
+    {
+        const int kr = min(mykey, p.t_kv - 1);
+        const __bf16* kp = p.k + ((size_t)kr * p.hkv + hk) * D + half * 8;
+        const __bf16* vp = p.v + ((size_t)kr * p.hkv + hk) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[ks] = *reinterpret_cast<const bf16x8*>(kp + ks * 16);
+            vf[ks] = *reinterpret_cast<const bf16x8*>(vp + ks * 16);
+        }
+    }
+    f32x16 dk_acc[DB], dv_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { dk_acc[db][r] = 0.f; dv_acc[db][r] = 0.f; }
+
+    const float cs = p.scale_log2e;
+    const int g_begin = p.key_range[2 * kt], g_end = p.key_range[2 * kt + 1];
+    const int k1 = min(k0 + BNK, p.t_kv);
+
+    for (int g = g_begin; g < g_end; ++g) {
+        const int4 gd = reinterpret_cast<const int4*>(p.group)[g];
+        if (!(gd.y > gd.x && gd.x < k1 && gd.y > k0)) continue;            // hull does not touch this tile
+        const bool full = (gd.z <= k0) && (k0 + BNK <= gd.w);              // every real row sees every key
+        const bool wave_live = (gd.x < kw0 + 32) && (gd.y > kw0);
+        for (int hh = 0; hh < G; ++hh) {
+            const int h = hk * G + hh;
+            __syncthreads();
+            // ---- stage the group's Q and dO rows (zeros for padding), LSE, delta, intervals
+            for (int ch = tid; ch < GR * CPR; ch += 256) {
+                const int r = ch / CPR, cc = ch % CPR;
+                const int rowi = g * GR + r;
+                const bool in = rowi < p.n_q;
+                const int rc = in ? rowi : p.n_q - 1;
+                const bool real = in && p.row_hi[rc] > 0;
+                i32x4 qq = {0, 0, 0, 0}, gg = {0, 0, 0, 0};
+                if (real) {
+                    qq = *reinterpret_cast<const i32x4*>(p.q + ((size_t)rc * p.hq + h) * D + cc * 8);
+                    gg = *reinterpret_cast<const i32x4*>(p.d_o + ((size_t)rc * p.hq + h) * D + cc * 8);
+                }
+                const int pc = swz<CPR>(r, cc) * 8;
+                *reinterpret_cast<i32x4*>(&Qs[r * D + pc]) = qq;
+                *reinterpret_cast<i32x4*>(&Os[r * D + pc]) = gg;
+            }
+            if (tid < GR) {
+                const int rowi = g * GR + tid;
+                const bool in = rowi < p.n_q;
+                const int rc = in ? rowi : p.n_q - 1;
+                const int rhi = in ? p.row_hi[rc] : 0;
+                const bool real = rhi > 0;
+                lo_s[tid] = real ? p.row_lo[rc] : kPadLo;
+                hi_s[tid] = rhi;
+                lse_s[tid] = real ? p.lse[(size_t)h * p.n_q + rc] * 1.4426950408889634f : INFINITY;
+                dl_s[tid] = real ? p.delta[(size_t)h * p.n_q + rc] : 0.f;
+            }
+            __syncthreads();
+            if (!wave_live) continue;
+
+#pragma unroll
+            for (int qb = 0; qb < GR / 32; ++qb) {
+                // S[q][k] = Q K^T, dP[q][k] = dO V^T : lane = key column, register = query row
+                f32x16 s, dp;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+                const int qr = qb * 32 + l32;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const int pc = swz<CPR>(qr, ks * 2 + half) * 8;
+                    const bf16x8 qa = *reinterpret_cast<const bf16x8*>(&Qs[qr * D + pc]);
+                    const bf16x8 ga = *reinterpret_cast<const bf16x8*>(&Os[qr * D + pc]);
+                    s = mfma32(qa, kf[ks], s);
+                    dp = mfma32(ga, vf[ks], dp);
+                }
+                float pr[16], ds[16];
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int qrow = qb * 32 + r4 * 8 + half * 4;
+                    const f32x4 ls = *reinterpret_cast<const f32x4*>(&lse_s[qrow]);
+                    const f32x4 dl = *reinterpret_cast<const f32x4*>(&dl_s[qrow]);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) pr[r4 * 4 + i] = fast_exp2(fmaf(s[r4 * 4 + i], cs, -ls[i]));
+                    if (!full) {
+                        const i32x4 l4 = *reinterpret_cast<const i32x4*>(&lo_s[qrow]);
+                        const i32x4 h4 = *reinterpret_cast<const i32x4*>(&hi_s[qrow]);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            pr[r4 * 4 + i] = (mykey >= l4[i] && mykey < h4[i]) ? pr[r4 * 4 + i] : 0.f;
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) ds[r4 * 4 + i] = pr[r4 * 4 + i] * (dp[r4 * 4 + i] - dl[i]);
+                }
+                bf16x8 pf[2], dsf[2];
+#pragma unroll
+                for (int cc = 0; cc < 2; ++cc) {
+                    pf[cc] = pack8(pr[8 * cc + 0], pr[8 * cc + 1], pr[8 * cc + 2], pr[8 * cc + 3], pr[8 * cc + 4],
+                                   pr[8 * cc + 5], pr[8 * cc + 6], pr[8 * cc + 7]);
+                    dsf[cc] = pack8(ds[8 * cc + 0], ds[8 * cc + 1], ds[8 * cc + 2], ds[8 * cc + 3], ds[8 * cc + 4],
+                                    ds[8 * cc + 5], ds[8 * cc + 6], ds[8 * cc + 7]);
+                }
+                // dV^T[d][k] += dO^T[d][q] P[q][k];  dK^T[d][k] += Q^T[d][q] dS[q][k]
+#pragma unroll
+                for (int cc = 0; cc < 2; ++cc) {
+                    const int q0 = qb * 32 + cc * 16 + half * 4 + (j16 >> 2);
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
+                        const int dsub = (j16 & 1) * 4;
+                        const int a0 = q0 * D + swz<CPR>(q0, dch) * 8 + dsub;
+                        const int a1 = (q0 + 8) * D + swz<CPR>(q0 + 8, dch) * 8 + dsub;
+                        const bf16x8 ga = cat4(lds_read_tr4(&Os[a0]), lds_read_tr4(&Os[a1]));
+                        const bf16x8 qa = cat4(lds_read_tr4(&Qs[a0]), lds_read_tr4(&Qs[a1]));
+                        dv_acc[db] = mfma32(ga, pf[cc], dv_acc[db]);
+                        dk_acc[db] = mfma32(qa, dsf[cc], dk_acc[db]);
+                    }
+                }
+            }
+        }
+    }
+
+    if (mykey < p.t_kv) {
+        __bf16* kp = p.dk + ((size_t)mykey * p.hkv + hk) * D;
+        __bf16* vp = p.dv + ((size_t)mykey * p.hkv + hk) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int d = db * 32 + r4 * 8 + half * 4;
+                *reinterpret_cast<bf16x4*>(kp + d) =
+                    pack4(dk_acc[db][r4 * 4 + 0] * p.scale, dk_acc[db][r4 * 4 + 1] * p.scale,
+                          dk_acc[db][r4 * 4 + 2] * p.scale, dk_acc[db][r4 * 4 + 3] * p.scale);
+                *reinterpret_cast<bf16x4*>(vp + d) = pack4(dv_acc[db][r4 * 4 + 0], dv_acc[db][r4 * 4 + 1],
+                                                           dv_acc[db][r4 * 4 + 2], dv_acc[db][r4 * 4 + 3]);
+            }
+    }
+}
+
 wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const void* q, const void* k,
                       const void* v, const void* o, const float* lse, const void* d_o, void* dq,
-                      void* dk, void* dv, char* ws, size_t off_delta, void* stream) {
-    return fail(WLB_ERR_UNSUPPORTED, "backward not built yet");
+                      void* dk, void* dv, char* ws, size_t off_delta, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    BwdParams p;
+    p.q = (const __bf16*)q; p.k = (const __bf16*)k; p.v = (const __bf16*)v;
+    p.o = (const __bf16*)o; p.d_o = (const __bf16*)d_o; p.lse = lse;
+    p.delta = (float*)(ws + off_delta);
+    p.dq = (__bf16*)dq; p.dk = (__bf16*)dk; p.dv = (__bf16*)dv;
+    p.row_lo = (const int32_t*)(ws + L.off_row_lo);
+    p.row_hi = (const int32_t*)(ws + L.off_row_hi);
+    p.group = (const int32_t*)(ws + L.off_group);
+    p.fwd_order = (const int32_t*)(ws + L.off_fwd_order);
+    p.key_order = (const int32_t*)(ws + L.off_key_order);
+    p.key_range = (const int32_t*)(ws + L.off_key_range);
+    p.n_q = d.n_q; p.t_kv = d.t_kv; p.hq = d.hq; p.hkv = d.hkv;
+    p.n_groups = L.n_groups; p.n_tiles = L.n_fwd_tiles; p.n_key_tiles = L.n_key_tiles;
+    p.scale = d.scale;
+    p.scale_log2e = d.scale * 1.4426950408889634f;
+
+    const size_t n_lanes = (size_t)d.n_q * d.hq * (d.head_dim / 8);
+    const unsigned grid_delta = (unsigned)((n_lanes + 255) / 256);
+    const unsigned grid_dq = (unsigned)((L.n_fwd_tiles + 7) / 8) * 8u * (unsigned)d.hq;
+    const unsigned grid_dkv = (unsigned)((L.n_key_tiles + 7) / 8) * 8u * (unsigned)d.hkv;
+    if (d.head_dim == 128) {
+        delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p);
+        dq_kernel<128, 2, 2><<<grid_dq, 128, 0, stream>>>(p);
+        dkv_kernel<128><<<grid_dkv, 256, 0, stream>>>(p);
+    } else {
+        delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p);
+        dq_kernel<64, 2, 2><<<grid_dq, 128, 0, stream>>>(p);
+        dkv_kernel<64><<<grid_dkv, 256, 0, stream>>>(p);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(WLB_ERR_HIP, "backward launch: %s", hipGetErrorString(e));
+    return WLB_OK;
 }
-}
+
+}  // namespace wlb

@@ -8,6 +8,7 @@ from paper_2503_17924_amd import binding as B
 from paper_2503_17924_amd import workloads as wl
 
 MAX_REL, MEAN_REL, LSE_ABS = 2e-2, 2e-3, 1e-2
+SCALE_FLOOR = 1e-3
 
 
 def check_close(name, got, ref, rows=None):
@@ -16,10 +17,10 @@ def check_close(name, got, ref, rows=None):
     if rows is not None:
         got, ref = got[rows], ref[rows]
     assert np.isfinite(got).all(), f"{name}: non-finite values"
-    scale = np.abs(ref).max()
-    if scale == 0:
-        assert np.abs(got).max() == 0, f"{name}: expected all zeros"
-        return 0.0, 0.0
+    # Errors are relative to the tensor's largest magnitude.  A tensor that is exactly zero in
+    # exact arithmetic (dQ when every document has one token: dS = dP - <dO, O> cancels) leaves
+    # only the bf16 rounding of O behind, so the scale is floored at 1e-3 (inputs are N(0,1)).
+    scale = max(np.abs(ref).max(), SCALE_FLOOR)
     err = np.abs(got - ref)
     mx, mean = err.max() / scale, err.mean() / scale
     assert mx <= MAX_REL, f"{name}: max err {mx:.3e} > {MAX_REL}"

@@ -133,3 +133,68 @@ def test_schedule_tables():
         # heaviest-first: the count of groups that touch a tile never increases by more than
         # the skipped (non-touching) groups inside the range; with sorted rows there are none
         assert kcount[0] == max(kcount)
+
+
+BWD_CASES = [
+    ([300, 45, 1, 700, 130], 4, 2, 128, 1),
+    ([64, 64, 128], 2, 2, 64, 1),
+    ([1] * 70, 2, 1, 128, 1),
+    ([1000], 8, 1, 128, 1),
+    ([3], 1, 1, 64, 1),
+    ([5, 900, 2, 3, 333, 64, 1, 77], 4, 4, 64, 2),
+    ([517, 3, 40, 1200], 8, 2, 128, 4),
+]
+
+
+@pytest.mark.parametrize("docs,hq,hkv,d,cp", BWD_CASES)
+def test_backward_matches_oracle(docs, hq, hkv, d, cp):
+    for r in range(cp):
+        c = _small(50 + r, docs, hq, hkv, d, cp, r, osh.PER_DOC_PADDED)
+        c.check_fwd(f" rank {r}")
+        c.check_bwd(f" rank {r}")
+
+
+def test_backward_per_sequence_sharding_and_rank_sum():
+    """Per-rank dK/dV partials add up to the unsharded gradient (what the reduce-scatter of
+    all-gather context parallelism would deliver)."""
+    docs = [700, 41, 3, 1000, 304]
+    cp = 4
+    full = _small(60, docs, 4, 1, 128)
+    full.run_fwd()
+    _, rdk, rdv = full.oracle_bwd()
+    dk_sum, dv_sum = np.zeros_like(rdk), np.zeros_like(rdv)
+    for r in range(cp):
+        c = _small(60, docs, 4, 1, 128, cp, r, osh.PER_SEQ)
+        c.check_fwd(f" rank {r}")
+        c.check_bwd(f" rank {r}")
+        _, dk, dv = c.run_bwd()
+        dk_sum += dk
+        dv_sum += dv
+    check_close("sum of dK partials", dk_sum, rdk)
+    check_close("sum of dV partials", dv_sum, rdv)
+
+
+def test_backward_rows_in_arbitrary_order_with_garbage_in_padding():
+    docs = [200, 333, 90]
+    w, tens = wl.small_case(61, docs, 4, 2, 128)
+    rng = np.random.default_rng(1)
+    q_idx = rng.permutation(sum(docs)).astype(np.int32)[:400]
+    q_idx[::13] = -1
+    c = Case(tens, q_idx, _cu(docs), 4, 2, 128, w.scale)
+    # padding rows may hold anything, including NaN and Inf bit patterns
+    pad = np.nonzero(q_idx < 0)[0]
+    for name in ("q", "do"):
+        t = c.dev[name].view(dtype=__import__("torch").int16)
+        t[pad[0::2]] = 0x7FC0          # NaN
+        t[pad[1::2]] = 0x7F80          # +Inf
+    c.check_fwd()
+    c.check_bwd()
+
+
+def test_backward_is_deterministic():
+    c = _small(62, [900, 50, 400], 4, 2, 128)
+    c.run_fwd()
+    a = c.run_bwd()
+    b = c.run_bwd()
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
