@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the WLB-LLM hot path on one MI355X.
+
+One step = one pass of the whole path over the 128K-context workload: the packer on the
+sequence's document list, then for each of the 8 emulated context-parallel ranks the sharding
+map (host), the tile schedule, attention forward and attention backward (device).  Inputs (the
+packed sequence's K/V and every rank's Q / dO rows) are resident in HBM before timing starts.
+
+Prints ONE JSON line: useful attention TFLOP/s forward+backward (only in-document causal
+query-key pairs are counted: 4*D flops forward and 10*D backward per pair and query head), the
+roofline record of the dominant kernel, per-rank latency max/mean under per-document and
+per-sequence sharding, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
+COST_A, COST_B = 6, 640000    # packer cost model, picoseconds per token^2 / per token
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=2, help="workload index (2 = the 128K CP=8 config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-seq", action="store_true", help="skip the per-sequence sharding comparison")
+    return ap.parse_args()
+
+
+class RankState:
+    """Everything one emulated CP rank keeps on the GPU."""
+
+    def __init__(self, B, torch, w, full, rank, mode, device):
+        self.rank, self.mode = rank, mode
+        sh = B.wlb_shard(w.doc_len, w.cp, rank, mode)
+        self.pairs = sh["useful_pairs"]
+        qi = sh["q_idx"]
+        self.n_q = len(qi)
+        self.q_idx_host = torch.from_numpy(qi.copy()).pin_memory()
+        self.attn = B.Attention(qi, sh["cu_seqlens_k"], w.total_tokens, w.hq, w.hkv, w.head_dim, w.scale, device)
+        rows = torch.from_numpy(np.maximum(qi, 0).astype(np.int64)).to(device)
+        self.q = full["q"].index_select(0, rows).contiguous()
+        self.do = full["do"].index_select(0, rows).contiguous()
+        self.o = torch.empty_like(self.q)
+        self.lse = torch.empty((w.hq, self.n_q), dtype=torch.float32, device=device)
+        self.dq = torch.empty_like(self.q)
+        self.dk = torch.empty_like(full["k"])
+        self.dv = torch.empty_like(full["v"])
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU (context-parallel ranks are emulated in turn); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2503_17924_amd import binding as B
+    from paper_2503_17924_amd import workloads as wl
+
+    B.lib()                       # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    device = torch.device("cuda:0")
+    w = wl.config(args.config)
+    if args.config == 3:
+        raise SystemExit("config 3 (packing pool) is covered by tests; bench configs: 1, 2, 4")
+    D, hq = w.head_dim, w.hq
+
+    t0 = time.time()
+    tens = w.tensors()
+    full = {n: B.bf16_bits_to_tensor(a, device) for n, a in tens.items()}
+    modes = [B.SHARD_PER_DOC_PADDED] + ([] if (args.no_per_seq or w.cp == 1) else [B.SHARD_PER_SEQ])
+    ranks = {m: [RankState(B, torch, w, full, r, m, device) for r in range(w.cp)] for m in modes}
+    setup_s = time.time() - t0
+
+    host_us = {"pack": 0.0, "shard": 0.0}
+
+    def step(states, record=None):
+        t = time.perf_counter()
+        B.wlb_pack(w.doc_len, 1, w.total_tokens, COST_A, COST_B)
+        host_us["pack"] += (time.perf_counter() - t) * 1e6
+        for st in states:
+            t = time.perf_counter()
+            sh = B.wlb_shard(w.doc_len, w.cp, st.rank, st.mode)
+            host_us["shard"] += (time.perf_counter() - t) * 1e6
+            st.q_idx_host.copy_(torch.from_numpy(sh["q_idx"]))
+            st.attn.q_idx.copy_(st.q_idx_host, non_blocking=True)
+            if record is not None:
+                e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+                e0.record()
+            st.attn.plan()
+            st.attn.forward(st.q, full["k"], full["v"], st.o, st.lse)
+            if record is not None:
+                e1.record()
+            if w.backward:
+                st.attn.backward(st.q, full["k"], full["v"], st.o, st.lse, st.do, st.dq, st.dk, st.dv)
+            if record is not None:
+                e2.record()
+                record.append((e0, e1, e2))
+
+    main_states = ranks[B.SHARD_PER_DOC_PADDED]
+    for _ in range(args.warmup):
+        step(main_states)
+    torch.cuda.synchronize()
+    host_us = {"pack": 0.0, "shard": 0.0}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(main_states)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    pairs = sum(st.pairs for st in main_states)
+    flops_fwd = 4.0 * D * hq * pairs
+    flops_bwd = 10.0 * D * hq * pairs if w.backward else 0.0
+    value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-rank latency (events on the stream the library launches on), both shardings
+    def rank_latency(states, reps=3):
+        lat = np.zeros((reps, len(states), 2))
+        for i in range(reps):
+            rec = []
+            step(states, rec)
+            torch.cuda.synchronize()
+            for j, (e0, e1, e2) in enumerate(rec):
+                lat[i, j] = (e0.elapsed_time(e1), e1.elapsed_time(e2))
+        return np.median(lat, axis=0)
+
+    per_rank = {}
+    for m in modes:
+        lat = rank_latency(ranks[m])
+        tot = lat.sum(axis=1)
+        per_rank["per_document" if m == B.SHARD_PER_DOC_PADDED else "per_sequence"] = {
+            "max_over_mean": float(tot.max() / tot.mean()), "fwd_ms": [round(x, 3) for x in lat[:, 0]],
+            "bwd_ms": [round(x, 3) for x in lat[:, 1]],
+            "pairs_max_over_mean": float(max(s.pairs for s in ranks[m]) / np.mean([s.pairs for s in ranks[m]]))}
+
+    # ---- per-kernel timing on rank 0 (the library's measurement flags isolate each kernel)
+    st = main_states[0]
+
+    def time_call(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return float(np.mean(ts))
+
+    kern = {}
+    kern["plan_ms"] = time_call(lambda: st.attn.plan())
+    kern["fwd_ms"] = time_call(lambda: st.attn.forward(st.q, full["k"], full["v"], st.o, st.lse))
+    if w.backward:
+        bw = lambda fl: st.attn.backward(st.q, full["k"], full["v"], st.o, st.lse, st.do, st.dq, st.dk, st.dv,
+                                         extra_flags=fl)
+        kern["delta_ms"] = time_call(lambda: bw(B.ATTN_BWD_SKIP_DQ | B.ATTN_BWD_SKIP_DKV))
+        kern["dq_ms"] = time_call(lambda: bw(B.ATTN_BWD_SKIP_DELTA | B.ATTN_BWD_SKIP_DKV))
+        kern["dkv_ms"] = time_call(lambda: bw(B.ATTN_BWD_SKIP_DELTA | B.ATTN_BWD_SKIP_DQ))
+    # algorithmic flops per launch: forward 4*D per pair and head; the dK/dV kernel carries the
+    # score and dP recomputation plus dK and dV (8*D); the dQ kernel adds dQ (2*D)
+    p0 = st.pairs
+    alg = {"fwd": 4.0 * D * hq * p0, "dkv": 8.0 * D * hq * p0, "dq": 2.0 * D * hq * p0}
+    tfl = {k: alg[k] / (kern[k + "_ms"] * 1e-3) / 1e12 for k in alg if k + "_ms" in kern}
+    dominant = max((k for k in tfl), key=lambda k: kern[k + "_ms"])
+    roofline = {"bound": "mfma", "kernel": {"fwd": "fwd_kernel", "dkv": "dkv_kernel", "dq": "dq_kernel"}[dominant],
+                "achieved": round(tfl[dominant], 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(tfl[dominant] / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "per_kernel_tflops": {k: round(v, 2) for k, v in tfl.items()},
+                "per_kernel_ms_rank0": {k: round(v, 4) for k, v in kern.items()}}
+
+    # ---- CPU oracle on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import attention as oat
+        qi = main_states[0].attn.q_idx.cpu().numpy()
+        real = np.nonzero(qi >= 0)[0]
+        stride = 16
+        sample = real[::stride]
+        f = {n: wl.bf16_bits_to_f64(tens[n]) for n in ("k", "v")}
+        qs = wl.bf16_bits_to_f64(tens["q"][qi[sample]])
+        dos = wl.bf16_bits_to_f64(tens["do"][qi[sample]])
+        cu = np.concatenate([[0], np.cumsum(w.doc_len)]).astype(np.int64)
+        spairs = oat.useful_pairs(qi[sample], cu)
+        t0 = time.perf_counter()
+        oat.attn_fwd(qs, f["k"], f["v"], qi[sample], cu, w.scale)
+        if w.backward:
+            oat.attn_bwd(qs, f["k"], f["v"], dos, qi[sample], cu, w.scale)
+        cpu_s = time.perf_counter() - t0
+        cpu_flops = (4.0 + (10.0 if w.backward else 0.0)) * D * hq * spairs
+        try:
+            import threadpoolctl
+            threads = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
+        except Exception:
+            threads = os.cpu_count()
+        cpu = {"value": round(cpu_flops / cpu_s / 1e12, 6), "unit": "useful TFLOP/s", "cores": int(threads),
+               "kind": "oracle", "seconds": round(cpu_s, 2),
+               "sample": f"rank 0, every {stride}th real query row ({len(sample)} rows, {spairs} pairs), all heads, fwd+bwd"}
+
+    out = {
+        "metric": "useful attn TFLOP/s fwd+bwd (% bf16 MFMA peak); per-CP-rank latency max/mean",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "tokens": w.total_tokens, "cp_ranks_emulated": w.cp, "hq": hq, "hkv": w.hkv,
+                   "head_dim": D, "n_docs": int(len(w.doc_len)), "longest_doc": int(w.doc_len.max()),
+                   "sharding": "per_document_padded", "useful_pairs": int(pairs)},
+        "pct_of_bf16_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "per_rank_latency": per_rank,
+        "host_us_per_step": {k: round(v / args.steps, 1) for k, v in host_us.items()},
+        "roofline": roofline, "cpu_baseline": cpu, "setup_s": round(setup_s, 1),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -131,7 +131,13 @@ enum {
      * wlb_attn_fwd/bwd without this flag) built for this same desc, q_idx and cu_seqlens_k:
      * skip rebuilding it.  The mask is the same for every layer and for forward and
      * backward, so one schedule serves them all. */
-    WLB_ATTN_REUSE_PLAN = 1
+    WLB_ATTN_REUSE_PLAN = 1,
+    /* Measurement aids for wlb_attn_bwd, so that one kernel can be timed or profiled alone:
+     * reuse the delta the previous backward call left in this workspace; do not run the dQ
+     * kernel (dq is left untouched); do not run the dK/dV kernel (dk, dv left untouched). */
+    WLB_ATTN_BWD_SKIP_DELTA = 2,
+    WLB_ATTN_BWD_SKIP_DQ = 4,
+    WLB_ATTN_BWD_SKIP_DKV = 8
 };
 
 /* Bytes of device workspace needed (256-byte aligned pointer expected).  The forward needs

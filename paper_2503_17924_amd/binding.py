@@ -20,6 +20,9 @@ WLB_OK = 0
 SHARD_PER_DOC_PADDED = 0
 SHARD_PER_SEQ = 1
 ATTN_REUSE_PLAN = 1
+ATTN_BWD_SKIP_DELTA = 2
+ATTN_BWD_SKIP_DQ = 4
+ATTN_BWD_SKIP_DKV = 8
 
 STATUS_NAMES = {0: "WLB_OK", 1: "WLB_ERR_INVALID_ARG", 2: "WLB_ERR_BUFFER_TOO_SMALL",
                 3: "WLB_ERR_UNSUPPORTED", 4: "WLB_ERR_HIP"}
@@ -56,6 +59,9 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2503_17924_amd.build`")
+        # torch ships its own HIP runtime; it must be in the process before libwlb.so is loaded
+        # so that both resolve to the same one (streams and pointers cross between them)
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.wlb_last_error.restype = C.c_char_p
         for name in EXPORTS[1:]:
@@ -211,7 +217,7 @@ class Attention:
         self.planned = True
         return o, lse
 
-    def backward(self, q, k, v, o, lse, d_o, dq=None, dk=None, dv=None):
+    def backward(self, q, k, v, o, lse, d_o, dq=None, dk=None, dv=None, extra_flags=0):
         torch = self.torch
         if dq is None:
             dq = torch.empty_like(q)
@@ -219,8 +225,10 @@ class Attention:
             dk = torch.empty_like(k)
         if dv is None:
             dv = torch.empty_like(v)
-        wlb_attn_bwd(self.desc_reuse if self.planned else self.desc, q, k, v, o, lse, d_o, self.q_idx, self.cu_k,
-                     dq, dk, dv, self.workspace)
+        desc = self.desc_reuse if self.planned else self.desc
+        if extra_flags:
+            desc = _desc(*self.shape, flags=desc.flags | extra_flags)
+        wlb_attn_bwd(desc, q, k, v, o, lse, d_o, self.q_idx, self.cu_k, dq, dk, dv, self.workspace)
         self.planned = True
         return dq, dk, dv
 

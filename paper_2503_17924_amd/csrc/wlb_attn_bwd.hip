@@ -421,14 +421,17 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     const unsigned grid_delta = (unsigned)((n_lanes + 255) / 256);
     const unsigned grid_dq = (unsigned)((L.n_fwd_tiles + 7) / 8) * 8u * (unsigned)d.hq;
     const unsigned grid_dkv = (unsigned)((L.n_key_tiles + 7) / 8) * 8u * (unsigned)d.hkv;
+    const bool do_delta = !(d.flags & WLB_ATTN_BWD_SKIP_DELTA);
+    const bool do_dq = !(d.flags & WLB_ATTN_BWD_SKIP_DQ);
+    const bool do_dkv = !(d.flags & WLB_ATTN_BWD_SKIP_DKV);
     if (d.head_dim == 128) {
-        delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p);
-        dq_kernel<128, 2, 2><<<grid_dq, 128, 0, stream>>>(p);
-        dkv_kernel<128><<<grid_dkv, 256, 0, stream>>>(p);
+        if (do_delta) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p);
+        if (do_dq) dq_kernel<128, 2, 2><<<grid_dq, 128, 0, stream>>>(p);
+        if (do_dkv) dkv_kernel<128><<<grid_dkv, 256, 0, stream>>>(p);
     } else {
-        delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p);
-        dq_kernel<64, 2, 2><<<grid_dq, 128, 0, stream>>>(p);
-        dkv_kernel<64><<<grid_dkv, 256, 0, stream>>>(p);
+        if (do_delta) delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p);
+        if (do_dq) dq_kernel<64, 2, 2><<<grid_dq, 128, 0, stream>>>(p);
+        if (do_dkv) dkv_kernel<64><<<grid_dkv, 256, 0, stream>>>(p);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(WLB_ERR_HIP, "backward launch: %s", hipGetErrorString(e));

@@ -29,7 +29,7 @@ wlb_status check_desc(const wlb_attn_desc* d) {
     const int64_t qe = (int64_t)d->n_q * d->hq * d->head_dim, ke = (int64_t)d->t_kv * d->hkv * d->head_dim;
     if (qe > 0x7fffffffLL * 8 || ke > 0x7fffffffLL * 8)
         return fail(WLB_ERR_UNSUPPORTED, "attention: tensor too large");
-    if (d->flags & ~WLB_ATTN_REUSE_PLAN) return fail(WLB_ERR_INVALID_ARG, "attention: unknown flag bits 0x%x", d->flags);
+    if (d->flags & ~(WLB_ATTN_REUSE_PLAN | WLB_ATTN_BWD_SKIP_DELTA | WLB_ATTN_BWD_SKIP_DQ | WLB_ATTN_BWD_SKIP_DKV)) return fail(WLB_ERR_INVALID_ARG, "attention: unknown flag bits 0x%x", d->flags);
     return WLB_OK;
 }
 

@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "wlb.h")).read()
     declared = set(re.findall(r"\b(wlb_[a-z_]+)\s*\(", header))
     assert declared == set(B.EXPORTS)
-    L = ctypes.CDLL(B.LIB_PATH)
+    L = B.lib()
     for name in declared:
         assert hasattr(L, name), name
 
