@@ -35,9 +35,16 @@ def build(verbose: bool = False, keep_asm: bool = False) -> str:
         cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
         if src.endswith(".cpp"):
             cmd[1:1] = ["-x", "hip"]
-        if keep_asm:
-            cmd += ["-save-temps=obj"]
+        if "attn" in src:
+            # kernels only: lets max() compile to bare v_max3 (no NaN quieting); the host-side
+            # argument checks live in other files and keep full NaN semantics
+            cmd += ["-fno-honor-nans"]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, cwd=bdir)))
+        if keep_asm and src.endswith(".hip"):
+            asm = [c for c in cmd if c != "-c"]
+            asm[asm.index("-o") + 1] = os.path.join(bdir, os.path.splitext(src)[0] + ".s")
+            asm += ["-S", "--cuda-device-only"]
+            procs.append((src + " (asm)", subprocess.Popen(asm, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, cwd=bdir)))
         objs.append(obj)
     for src, p in procs:
         out, _ = p.communicate()

@@ -24,12 +24,6 @@
 
 namespace wlb {
 
-// physical 16-byte chunk of logical chunk `cc` in row `r` (CPR chunks per row)
-template <int CPR>
-__device__ __forceinline__ int swz(int r, int cc) {
-    return cc ^ ((((r & 3) << 2) | ((r >> 2) & 3)) & (CPR - 1));
-}
-
 struct BwdParams {
     const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* o; const __bf16* d_o;
     const float* lse; float* delta;

@@ -32,6 +32,12 @@ __device__ __forceinline__ bf16x4 lds_read_tr4(const __bf16* p) {
     return __builtin_bit_cast(bf16x4, r);
 }
 
+// same, from a 32-bit LDS address
+__device__ __forceinline__ bf16x4 lds_read_tr4_at(uint32_t lds_addr) {
+    s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((WLB_LDS s16x4*)(uintptr_t)lds_addr);
+    return __builtin_bit_cast(bf16x4, r);
+}
+
 __device__ __forceinline__ bf16x8 cat4(bf16x4 a, bf16x4 b) {
     return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
 }
@@ -59,6 +65,78 @@ __device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3) 
     r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;
     return r;
 }
+
+// XOR swizzle of the 16-byte chunks of an unpadded row-major LDS tile whose rows hold CPR
+// chunks: logical chunk cc of row r is stored at chunk swz(r, cc).  With 256-byte rows it
+// makes both access patterns of the kernels bank-conflict free: 16 rows x one chunk (b128
+// MFMA operand reads) and 4 rows x 4 consecutive chunks (transpose reads).
+template <int CPR>
+__device__ __forceinline__ int swz(int r, int cc) {
+    return cc ^ ((((r & 3) << 2) | ((r >> 2) & 3)) & (CPR - 1));
+}
+
+// Asynchronous global -> LDS copy of a tile of ROWS rows x D bf16 (rows contiguous in LDS,
+// 16-byte chunks swizzled), issued by all NW wavefronts of a workgroup.  Each instruction is a
+// buffer load that moves 64 x 16 bytes straight into LDS without passing through registers;
+// lane i's 16 bytes land at (instruction's LDS base) + 16*i, so the swizzle is applied on the
+// global side.  The buffer descriptor bounds the tensor: rows past its end read as zeros, so
+// ragged last tiles need no clamping.  Completion: wait_vmem() + workgroup barrier.
+struct BufRsrc {
+    i32x4 r;   // buffer descriptor: base address, stride 0, num_records = bytes, raw 32-bit format
+    __device__ __forceinline__ void init(const void* base, uint32_t bytes) {
+        const uint64_t a = (uint64_t)(uintptr_t)base;
+        r[0] = (int)(uint32_t)a;
+        r[1] = (int)(uint32_t)((a >> 32) & 0xffffu);
+        r[2] = (int)bytes;
+        r[3] = 0x00020000;
+    }
+};
+
+// One buffer_load_dwordx4 ... lds: 64 lanes x 16 bytes from (descriptor base + soff + voff)
+// into LDS at lds_addr + 16*lane.  Written as inline assembly so that the compiler does not
+// serialise later LDS reads of OTHER buffers behind this copy; the callers order reads of the
+// destination buffer themselves (wait_vmem + barrier).
+__device__ __forceinline__ void dma_issue_1k(const i32x4& rsrc, uint32_t lds_addr, int voff, uint32_t soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory");
+}
+
+template <int D, int ROWS, int NW>
+struct TileDma {
+    static constexpr int CPR = D / 8;         // 16-byte chunks per row
+    static constexpr int RPI = 64 / CPR;      // rows per instruction
+    static constexpr int NI = ROWS / RPI;     // instructions per tile
+    static constexpr int PER = NI / NW;       // instructions per wavefront
+    static_assert(NI % NW == 0, "tile must split evenly over the wavefronts");
+    int voff[PER];                            // per-lane byte offsets inside the instruction's rows
+    uint32_t row_bytes;
+
+    __device__ __forceinline__ void init(int wave, int lane, uint32_t stride_elems) {
+        row_bytes = stride_elems * 2;
+#pragma unroll
+        for (int n = 0; n < PER; ++n) {
+            const int blk = wave * PER + n;
+            const int ri = lane / CPR;
+            const int cc = swz<CPR>(blk * RPI + ri, lane % CPR);   // source chunk for this LDS slot
+            voff[n] = ri * (int)row_bytes + cc * 16;
+        }
+    }
+    // rows row0 .. row0+ROWS-1 of the tensor -> lds_tile (ROWS * D * 2 bytes)
+    __device__ __forceinline__ void issue(const BufRsrc& rs, __bf16* lds_tile, int row0, int wave) const {
+#pragma unroll
+        for (int n = 0; n < PER; ++n) {
+            const int blk = wave * PER + n;
+            const uint32_t soff = (uint32_t)(row0 + blk * RPI) * row_bytes;
+            const uint32_t lds_addr = (uint32_t)(uintptr_t)(WLB_LDS void*)(lds_tile + blk * 512);
+            dma_issue_1k(rs.r, __builtin_amdgcn_readfirstlane(lds_addr), voff[n],
+                         __builtin_amdgcn_readfirstlane(soff));
+        }
+    }
+};
+
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
 constexpr int kPadLo = 0x7fffffff;  // row_lo of a padding row (row_hi = 0): no key satisfies lo <= k < hi
 

@@ -27,8 +27,9 @@ wlb_status check_desc(const wlb_attn_desc* d) {
     if (d->head_dim != 64 && d->head_dim != 128)
         return fail(WLB_ERR_UNSUPPORTED, "attention: head_dim=%d (64 and 128 are built)", d->head_dim);
     const int64_t qe = (int64_t)d->n_q * d->hq * d->head_dim, ke = (int64_t)d->t_kv * d->hkv * d->head_dim;
-    if (qe > 0x7fffffffLL * 8 || ke > 0x7fffffffLL * 8)
-        return fail(WLB_ERR_UNSUPPORTED, "attention: tensor too large");
+    // tensors are addressed through 32-bit buffer descriptors: each must stay under 4 GiB
+    if (qe * 2 >= (1LL << 32) || ke * 2 >= (1LL << 32))
+        return fail(WLB_ERR_UNSUPPORTED, "attention: a tensor of 4 GiB or more is not supported");
     if (d->flags & ~(WLB_ATTN_REUSE_PLAN | WLB_ATTN_BWD_SKIP_DELTA | WLB_ATTN_BWD_SKIP_DQ | WLB_ATTN_BWD_SKIP_DKV)) return fail(WLB_ERR_INVALID_ARG, "attention: unknown flag bits 0x%x", d->flags);
     return WLB_OK;
 }
