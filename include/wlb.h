@@ -164,6 +164,7 @@ typedef struct {
     int32_t bwd_key_tile, n_key_tiles;
     size_t  off_row_lo, off_row_hi;      /* int32 [n_q]: visible keys are [lo, hi); pads: lo > hi */
     size_t  off_group;                   /* int32 [n_groups][4] */
+    size_t  off_group_real;              /* int32 [n_groups]: real (non-padding, in-range) rows in the group */
     size_t  off_fwd_order;               /* int32 [n_fwd_tiles] */
     size_t  off_fwd_cost;                /* int32 [n_fwd_tiles]: key tiles each query tile visits */
     size_t  off_key_order;               /* int32 [n_key_tiles] */

@@ -28,7 +28,7 @@ struct BwdParams {
     const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* o; const __bf16* d_o;
     const float* lse; float* delta;
     __bf16* dq; __bf16* dk; __bf16* dv;
-    const int32_t* row_lo; const int32_t* row_hi; const int32_t* group;
+    const int32_t* row_lo; const int32_t* row_hi; const int32_t* group; const int32_t* group_real;
     const int32_t* fwd_order; const int32_t* key_order; const int32_t* key_range;
     int n_q, t_kv, hq, hkv, n_groups, n_tiles, n_key_tiles;
     float scale_log2e, scale;
@@ -224,18 +224,191 @@ __global__ void __launch_bounds__(NW * 64) dq_kernel(const BwdParams p) {
 }
 
 // ------------------------------------------------------------------------------------------
+// dQ, four wavefronts x 32 rows, two workgroups per CU: K and V tiles of 64 keys arrive by
+// asynchronous global->LDS copies (double buffered, one barrier per tile); per block of 32
+// keys a wavefront computes S^T = K Q^T and dP^T = V dO^T (lane = its query column), forms
+// dS^T = P^T o (dP^T - delta) in registers and accumulates dQ^T += K^T dS^T with K^T read
+// from the same swizzled K tile by transpose reads.
+template <int D>
+__global__ void __launch_bounds__(256, 2) dq_pipe_kernel(const BwdParams p) {
+    constexpr int NW = 4, BM = 128, BN = 64;
+    static_assert(BM == kFwdTileRows, "tile rows must match the schedule");
+    constexpr int KS = D / 16, DB = D / 32, CPR = D / 8, ROWB = D * 2, TILEB = BN * ROWB;
+
+    __shared__ __attribute__((aligned(1024))) char smem[4 * TILEB];   // K0 | K1 | V0 | V1
+
+    const int G = p.hq / p.hkv;
+    const int x = blockIdx.x & 7;
+    int y = blockIdx.x >> 3;
+    const int hh = y % G; y /= G;
+    const int hk = y % p.hkv;
+    const int c = y / p.hkv;
+    const int rank = c * 8 + x;
+    if (rank >= p.n_tiles) return;
+    const int tile = p.fwd_order[rank];
+    const int h = hk * G + hh;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int j16 = lane & 15, gi = (lane >> 4) & 1;
+
+    int k_lo = kPadLo, k_hi = 0, max_lo = 0, min_hi = kPadLo;
+    for (int j = 0; j < BM / kGroupRows; ++j) {
+        const int g = tile * (BM / kGroupRows) + j;
+        if (g < p.n_groups) {
+            const int4 d = reinterpret_cast<const int4*>(p.group)[g];
+            if (d.y > d.x) { k_lo = min(k_lo, d.x); k_hi = max(k_hi, d.y); max_lo = max(max_lo, d.z); min_hi = min(min_hi, d.w); }
+        }
+    }
+    int jb = 0, je = 0, fb = 0, fe = 0;
+    if (k_hi > k_lo) {
+        jb = k_lo / BN; je = (k_hi + BN - 1) / BN;
+        fb = (max_lo + BN - 1) / BN; fe = min_hi / BN;
+        if (fe < fb) fe = fb;
+    }
+
+    const uint32_t kv_row = (uint32_t)p.hkv * D;
+    const uint32_t kv_bytes = ((uint32_t)p.t_kv * kv_row - (uint32_t)hk * D) * 2u;
+    BufRsrc krs, vrs;
+    krs.init(p.k + (size_t)hk * D, kv_bytes);
+    vrs.init(p.v + (size_t)hk * D, kv_bytes);
+    TileDma<D, BN, NW> dma;
+    dma.init(wave, lane, kv_row);
+    auto tile_ptr = [&](int which) { return reinterpret_cast<__bf16*>(smem + which * TILEB); };
+    if (jb < je) {
+        dma.issue(krs, tile_ptr(0), jb * BN, wave);
+        dma.issue(vrs, tile_ptr(2), jb * BN, wave);
+    }
+
+    const int row = tile * BM + wave * 32 + l32;
+    const bool in = row < p.n_q;
+    const int rc = in ? row : p.n_q - 1;
+    const int lo = in ? p.row_lo[rc] : kPadLo;
+    const int hi = in ? p.row_hi[rc] : 0;
+    const bool real = hi > 0;
+    // padding rows: zero operands and LSE = +inf make P, dS and dQ exactly 0
+    const float lsec = real ? p.lse[(size_t)h * p.n_q + rc] * 1.4426950408889634f : INFINITY;
+    const float dl = real ? p.delta[(size_t)h * p.n_q + rc] : 0.f;
+    bf16x8 qf[KS], dof[KS];
+    {
+        const __bf16* qp = p.q + ((size_t)rc * p.hq + h) * D + half * 8;
+        const __bf16* gp = p.d_o + ((size_t)rc * p.hq + h) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 a = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+            bf16x8 g = *reinterpret_cast<const bf16x8*>(gp + ks * 16);
+            if (!real) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { a[i] = (__bf16)0.f; g[i] = (__bf16)0.f; }
+            }
+            qf[ks] = a; dof[ks] = g;
+        }
+    }
+
+    int naddr[KS], taddr[DB][2];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) naddr[ks] = l32 * ROWB + swz<CPR>(l32, ks * 2 + half) * 16;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int key = t * 8 + half * 4 + (j16 >> 2);
+            const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
+            taddr[db][t] = key * ROWB + swz<CPR>(key, dch) * 16 + (j16 & 1) * 8;
+        }
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
+
+    f32x16 acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+    const float cs = p.scale_log2e;
+
+    for (int j = jb; j < je; ++j) {
+        const int cur = (j - jb) & 1;
+        wait_vmem();
+        __syncthreads();
+        if (j + 1 < je) {
+            dma.issue(krs, tile_ptr(cur ^ 1), (j + 1) * BN, wave);
+            dma.issue(vrs, tile_ptr(2 + (cur ^ 1)), (j + 1) * BN, wave);
+        }
+        const uint32_t kb_base = smem_base + cur * TILEB, vb_base = smem_base + (2 + cur) * TILEB;
+        const bool partial = (j < fb) || (j >= fe);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            f32x16 s, dp;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8 ka = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(kb_base + naddr[ks] + kb * 32 * ROWB));
+                const bf16x8 va = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(vb_base + naddr[ks] + kb * 32 * ROWB));
+                s = mfma32(ka, qf[ks], s);
+                dp = mfma32(va, dof[ks], dp);
+            }
+            float ds[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float pr = fast_exp2(fmaf(s[r], cs, -lsec));
+                ds[r] = pr * (dp[r] - dl);
+            }
+            if (partial) {
+                asm volatile("");   // keep the mask a branch
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = j * BN + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                    ds[r] = (key >= lo && key < hi) ? ds[r] : 0.f;
+                }
+            }
+            bf16x8 dsf[2];
+            dsf[0] = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
+            dsf[1] = pack8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+                const int koff = (kb * 32 + cc * 16) * ROWB;
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const bf16x8 a = cat4(lds_read_tr4_at(kb_base + taddr[db][0] + koff),
+                                          lds_read_tr4_at(kb_base + taddr[db][1] + koff));
+                    acc[db] = mfma32(a, dsf[cc], acc[db]);
+                }
+            }
+        }
+    }
+
+    if (in) {
+        __bf16* op = p.dq + ((size_t)row * p.hq + h) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int d = db * 32 + r4 * 8 + half * 4;
+                bf16x4 out;
+                if (real) out = pack4(acc[db][r4 * 4 + 0] * p.scale, acc[db][r4 * 4 + 1] * p.scale,
+                                      acc[db][r4 * 4 + 2] * p.scale, acc[db][r4 * 4 + 3] * p.scale);
+                else out = pack4(0.f, 0.f, 0.f, 0.f);
+                *reinterpret_cast<bf16x4*>(op + d) = out;
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // dK/dV: one workgroup = 128 keys x one KV head; wavefront w owns keys [k0+32w, k0+32w+32).
+// The row groups that can see the tile stream through LDS, one (group, query head) stage at a
+// time: Q and dO rows by asynchronous global->LDS copies into the buffer not being computed
+// on, LSE / delta / key intervals through registers one stage ahead.  One barrier per stage.
 template <int D>
 __global__ void __launch_bounds__(256) dkv_kernel(const BwdParams p) {
     constexpr int BNK = kBwdKeyTile, GR = kGroupRows, KS = D / 16, DB = D / 32, CPR = D / 8;
+    constexpr int ROWB = D * 2, TILEB = GR * ROWB;
     static_assert(BNK == 128 && GR == 64, "tiling");
 
-    __shared__ __attribute__((aligned(16))) __bf16 Qs[GR * D];     // swizzled
-    __shared__ __attribute__((aligned(16))) __bf16 Os[GR * D];     // dO, swizzled
-    __shared__ __attribute__((aligned(16))) float lse_s[GR];       // LSE * log2(e); +inf for padding rows
-    __shared__ __attribute__((aligned(16))) float dl_s[GR];
-    __shared__ __attribute__((aligned(16))) int lo_s[GR];
-    __shared__ __attribute__((aligned(16))) int hi_s[GR];
+    __shared__ __attribute__((aligned(1024))) char smem[4 * TILEB];          // Q0 | Q1 | dO0 | dO1, swizzled
+    __shared__ __attribute__((aligned(16))) float lse_s[2][GR];              // LSE * log2(e); +inf for padding rows
+    __shared__ __attribute__((aligned(16))) float dl_s[2][GR];
+    __shared__ __attribute__((aligned(16))) int lo_s[2][GR];
+    __shared__ __attribute__((aligned(16))) int hi_s[2][GR];
 
     const int G = p.hq / p.hkv;
     const int x = blockIdx.x & 7;
@@ -272,59 +445,107 @@ __global__ void __launch_bounds__(256) dkv_kernel(const BwdParams p) {
         for (int r = 0; r < 16; ++r) { dk_acc[db][r] = 0.f; dv_acc[db][r] = 0.f; }
 
     const float cs = p.scale_log2e;
-    const int g_begin = p.key_range[2 * kt], g_end = p.key_range[2 * kt + 1];
+    const int g_end = p.key_range[2 * kt + 1];
     const int k1 = min(k0 + BNK, p.t_kv);
 
-    for (int g = g_begin; g < g_end; ++g) {
+    // first group at or after g whose hull touches this key tile (g_end if none)
+    auto next_group = [&](int g) {
+        for (; g < g_end; ++g) {
+            const int4 gd = reinterpret_cast<const int4*>(p.group)[g];
+            if (gd.y > gd.x && gd.x < k1 && gd.y > k0) break;
+        }
+        return g;
+    };
+
+    const uint32_t q_row = (uint32_t)p.hq * D;
+    const uint32_t q_total = (uint32_t)p.n_q * q_row * 2u;
+    TileDma<D, GR, 4> dma;
+    dma.init(wave, lane, q_row);
+    auto tile_ptr = [&](int which) { return reinterpret_cast<__bf16*>(smem + which * TILEB); };
+    auto issue_stage = [&](int g, int h, int buf) {
+        BufRsrc qrs, ors;
+        qrs.init(p.q + (size_t)h * D, q_total - (uint32_t)h * ROWB);
+        ors.init(p.d_o + (size_t)h * D, q_total - (uint32_t)h * ROWB);
+        dma.issue(qrs, tile_ptr(buf), g * GR, wave);
+        dma.issue(ors, tile_ptr(2 + buf), g * GR, wave);
+    };
+    // per-row scalars of a stage, fetched by the first 64 threads one stage ahead
+    float r_lse = INFINITY, r_dl = 0.f;
+    int r_lo = kPadLo, r_hi = 0;
+    auto load_small = [&](int g, int h) {
+        if (tid < GR) {
+            const int rowi = g * GR + tid;
+            const bool inr = rowi < p.n_q;
+            const int rc = inr ? rowi : p.n_q - 1;
+            r_hi = inr ? p.row_hi[rc] : 0;
+            const bool real = r_hi > 0;
+            r_lo = real ? p.row_lo[rc] : kPadLo;
+            r_lse = real ? p.lse[(size_t)h * p.n_q + rc] * 1.4426950408889634f : INFINITY;
+            r_dl = real ? p.delta[(size_t)h * p.n_q + rc] : 0.f;
+        }
+    };
+
+    // LDS offsets (bytes inside a tile) of the two access patterns
+    int naddr[KS], taddr[DB][2];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) naddr[ks] = l32 * ROWB + swz<CPR>(l32, ks * 2 + half) * 16;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int qq = t * 8 + half * 4 + (j16 >> 2);
+            const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
+            taddr[db][t] = qq * ROWB + swz<CPR>(qq, dch) * 16 + (j16 & 1) * 8;
+        }
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
+
+    int g = next_group(p.key_range[2 * kt]);
+    int hh = 0, buf = 0;
+    if (g < g_end) {
+        issue_stage(g, hk * G, 0);
+        load_small(g, hk * G);
+    }
+    while (g < g_end) {
+        // next stage
+        int gn = g, hn = hh + 1;
+        if (hn == G) { hn = 0; gn = next_group(g + 1); }
         const int4 gd = reinterpret_cast<const int4*>(p.group)[g];
-        if (!(gd.y > gd.x && gd.x < k1 && gd.y > k0)) continue;            // hull does not touch this tile
         const bool full = (gd.z <= k0) && (k0 + BNK <= gd.w);              // every real row sees every key
         const bool wave_live = (gd.x < kw0 + 32) && (gd.y > kw0);
-        for (int hh = 0; hh < G; ++hh) {
-            const int h = hk * G + hh;
-            __syncthreads();
-            // ---- stage the group's Q and dO rows (zeros for padding), LSE, delta, intervals
-            for (int ch = tid; ch < GR * CPR; ch += 256) {
-                const int r = ch / CPR, cc = ch % CPR;
-                const int rowi = g * GR + r;
-                const bool in = rowi < p.n_q;
-                const int rc = in ? rowi : p.n_q - 1;
-                const bool real = in && p.row_hi[rc] > 0;
-                i32x4 qq = {0, 0, 0, 0}, gg = {0, 0, 0, 0};
-                if (real) {
-                    qq = *reinterpret_cast<const i32x4*>(p.q + ((size_t)rc * p.hq + h) * D + cc * 8);
-                    gg = *reinterpret_cast<const i32x4*>(p.d_o + ((size_t)rc * p.hq + h) * D + cc * 8);
-                }
-                const int pc = swz<CPR>(r, cc) * 8;
-                *reinterpret_cast<i32x4*>(&Qs[r * D + pc]) = qq;
-                *reinterpret_cast<i32x4*>(&Os[r * D + pc]) = gg;
-            }
-            if (tid < GR) {
-                const int rowi = g * GR + tid;
-                const bool in = rowi < p.n_q;
-                const int rc = in ? rowi : p.n_q - 1;
-                const int rhi = in ? p.row_hi[rc] : 0;
-                const bool real = rhi > 0;
-                lo_s[tid] = real ? p.row_lo[rc] : kPadLo;
-                hi_s[tid] = rhi;
-                lse_s[tid] = real ? p.lse[(size_t)h * p.n_q + rc] * 1.4426950408889634f : INFINITY;
-                dl_s[tid] = real ? p.delta[(size_t)h * p.n_q + rc] : 0.f;
-            }
-            __syncthreads();
-            if (!wave_live) continue;
+        const bool has_pads = p.group_real[g] < min(GR, p.n_q - g * GR);
 
+        if (tid < GR) { lse_s[buf][tid] = r_lse; dl_s[buf][tid] = r_dl; lo_s[buf][tid] = r_lo; hi_s[buf][tid] = r_hi; }
+        wait_vmem();
+        __syncthreads();      // stage (g, hh) is in LDS; everyone has left the other buffer
+        if (gn < g_end) {
+            issue_stage(gn, hk * G + hn, buf ^ 1);
+            load_small(gn, hk * G + hn);
+        }
+        if (has_pads) {
+            // padding rows may hold anything: clear them so they cannot poison the MFMAs
+            const int r = tid >> 2, part = tid & 3;
+            if (hi_s[buf][r] == 0) {
+                const i32x4 z = {0, 0, 0, 0};
 #pragma unroll
+                for (int i = 0; i < CPR / 4; ++i) {
+                    *reinterpret_cast<i32x4*>(smem + buf * TILEB + r * ROWB + (part * (CPR / 4) + i) * 16) = z;
+                    *reinterpret_cast<i32x4*>(smem + (2 + buf) * TILEB + r * ROWB + (part * (CPR / 4) + i) * 16) = z;
+                }
+            }
+            __syncthreads();
+        }
+        if (wave_live) {
+            const uint32_t qb_base = smem_base + buf * TILEB, ob_base = smem_base + (2 + buf) * TILEB;
+#pragma unroll 1
             for (int qb = 0; qb < GR / 32; ++qb) {
                 // S[q][k] = Q K^T, dP[q][k] = dO V^T : lane = key column, register = query row
                 f32x16 s, dp;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-                const int qr = qb * 32 + l32;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const int pc = swz<CPR>(qr, ks * 2 + half) * 8;
-                    const bf16x8 qa = *reinterpret_cast<const bf16x8*>(&Qs[qr * D + pc]);
-                    const bf16x8 ga = *reinterpret_cast<const bf16x8*>(&Os[qr * D + pc]);
+                    const bf16x8 qa = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(qb_base + naddr[ks] + qb * 32 * ROWB));
+                    const bf16x8 ga = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(ob_base + naddr[ks] + qb * 32 * ROWB));
                     s = mfma32(qa, kf[ks], s);
                     dp = mfma32(ga, vf[ks], dp);
                 }
@@ -332,13 +553,14 @@ __global__ void __launch_bounds__(256) dkv_kernel(const BwdParams p) {
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const int qrow = qb * 32 + r4 * 8 + half * 4;
-                    const f32x4 ls = *reinterpret_cast<const f32x4*>(&lse_s[qrow]);
-                    const f32x4 dl = *reinterpret_cast<const f32x4*>(&dl_s[qrow]);
+                    const f32x4 ls = *reinterpret_cast<const f32x4*>(&lse_s[buf][qrow]);
+                    const f32x4 dl = *reinterpret_cast<const f32x4*>(&dl_s[buf][qrow]);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) pr[r4 * 4 + i] = fast_exp2(fmaf(s[r4 * 4 + i], cs, -ls[i]));
                     if (!full) {
-                        const i32x4 l4 = *reinterpret_cast<const i32x4*>(&lo_s[qrow]);
-                        const i32x4 h4 = *reinterpret_cast<const i32x4*>(&hi_s[qrow]);
+                        asm volatile("");   // keep the mask a branch
+                        const i32x4 l4 = *reinterpret_cast<const i32x4*>(&lo_s[buf][qrow]);
+                        const i32x4 h4 = *reinterpret_cast<const i32x4*>(&hi_s[buf][qrow]);
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
                             pr[r4 * 4 + i] = (mykey >= l4[i] && mykey < h4[i]) ? pr[r4 * 4 + i] : 0.f;
@@ -357,21 +579,20 @@ __global__ void __launch_bounds__(256) dkv_kernel(const BwdParams p) {
                 // dV^T[d][k] += dO^T[d][q] P[q][k];  dK^T[d][k] += Q^T[d][q] dS[q][k]
 #pragma unroll
                 for (int cc = 0; cc < 2; ++cc) {
-                    const int q0 = qb * 32 + cc * 16 + half * 4 + (j16 >> 2);
+                    const int qoff = (qb * 32 + cc * 16) * ROWB;
 #pragma unroll
                     for (int db = 0; db < DB; ++db) {
-                        const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
-                        const int dsub = (j16 & 1) * 4;
-                        const int a0 = q0 * D + swz<CPR>(q0, dch) * 8 + dsub;
-                        const int a1 = (q0 + 8) * D + swz<CPR>(q0 + 8, dch) * 8 + dsub;
-                        const bf16x8 ga = cat4(lds_read_tr4(&Os[a0]), lds_read_tr4(&Os[a1]));
-                        const bf16x8 qa = cat4(lds_read_tr4(&Qs[a0]), lds_read_tr4(&Qs[a1]));
+                        const bf16x8 ga = cat4(lds_read_tr4_at(ob_base + taddr[db][0] + qoff),
+                                               lds_read_tr4_at(ob_base + taddr[db][1] + qoff));
+                        const bf16x8 qa = cat4(lds_read_tr4_at(qb_base + taddr[db][0] + qoff),
+                                               lds_read_tr4_at(qb_base + taddr[db][1] + qoff));
                         dv_acc[db] = mfma32(ga, pf[cc], dv_acc[db]);
                         dk_acc[db] = mfma32(qa, dsf[cc], dk_acc[db]);
                     }
                 }
             }
         }
+        g = gn; hh = hn; buf ^= 1;
     }
 
     if (mykey < p.t_kv) {
@@ -403,6 +624,7 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.row_lo = (const int32_t*)(ws + L.off_row_lo);
     p.row_hi = (const int32_t*)(ws + L.off_row_hi);
     p.group = (const int32_t*)(ws + L.off_group);
+    p.group_real = (const int32_t*)(ws + L.off_group_real);
     p.fwd_order = (const int32_t*)(ws + L.off_fwd_order);
     p.key_order = (const int32_t*)(ws + L.off_key_order);
     p.key_range = (const int32_t*)(ws + L.off_key_range);
@@ -420,11 +642,11 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     const bool do_dkv = !(d.flags & WLB_ATTN_BWD_SKIP_DKV);
     if (d.head_dim == 128) {
         if (do_delta) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p);
-        if (do_dq) dq_kernel<128, 2, 2><<<grid_dq, 128, 0, stream>>>(p);
+        if (do_dq) dq_pipe_kernel<128><<<grid_dq, 256, 0, stream>>>(p);
         if (do_dkv) dkv_kernel<128><<<grid_dkv, 256, 0, stream>>>(p);
     } else {
         if (do_delta) delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p);
-        if (do_dq) dq_kernel<64, 2, 2><<<grid_dq, 128, 0, stream>>>(p);
+        if (do_dq) dq_pipe_kernel<64><<<grid_dq, 256, 0, stream>>>(p);
         if (do_dkv) dkv_kernel<64><<<grid_dkv, 256, 0, stream>>>(p);
     }
     hipError_t e = hipGetLastError();

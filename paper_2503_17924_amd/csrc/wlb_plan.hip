@@ -46,6 +46,7 @@ void plan_layout(const wlb_attn_desc& d, wlb_plan_layout* L) {
     L->off_row_lo = take(sizeof(int32_t) * d.n_q);
     L->off_row_hi = take(sizeof(int32_t) * d.n_q);
     L->off_group = take(sizeof(int32_t) * 4 * L->n_groups);
+    L->off_group_real = take(sizeof(int32_t) * L->n_groups);
     L->off_fwd_order = take(sizeof(int32_t) * L->n_fwd_tiles);
     L->off_fwd_cost = take(sizeof(int32_t) * L->n_fwd_tiles);
     L->off_key_order = take(sizeof(int32_t) * L->n_key_tiles);
@@ -79,7 +80,8 @@ __device__ __forceinline__ int wave_sum(int v) {
 __global__ void __launch_bounds__(256) plan_rows_kernel(const int32_t* __restrict__ q_idx,
                                                         const int32_t* __restrict__ cu, int n_q, int t_kv,
                                                         int n_docs, int n_groups, int32_t* __restrict__ row_lo,
-                                                        int32_t* __restrict__ row_hi, int32_t* __restrict__ group) {
+                                                        int32_t* __restrict__ row_hi, int32_t* __restrict__ group,
+                                                        int32_t* __restrict__ group_real) {
     const int lane = threadIdx.x & 63;
     const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (g >= n_groups) return;
@@ -111,6 +113,8 @@ __global__ void __launch_bounds__(256) plan_rows_kernel(const int32_t* __restric
         else out = make_int4(k_lo, k_hi, max_lo, min_hi);
         reinterpret_cast<int4*>(group)[g] = out;
     }
+    const int n_real = wave_sum(real ? 1 : 0);
+    if (lane == 0) group_real[g] = n_real;
 }
 
 // cost of a forward tile = number of 64-key tiles between the hull's ends
@@ -171,13 +175,14 @@ wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const i
     int32_t* row_lo = (int32_t*)(ws + L.off_row_lo);
     int32_t* row_hi = (int32_t*)(ws + L.off_row_hi);
     int32_t* group = (int32_t*)(ws + L.off_group);
+    int32_t* group_real = (int32_t*)(ws + L.off_group_real);
     int32_t* fwd_order = (int32_t*)(ws + L.off_fwd_order);
     int32_t* fwd_cost = (int32_t*)(ws + L.off_fwd_cost);
     int32_t* key_order = (int32_t*)(ws + L.off_key_order);
     int32_t* key_range = (int32_t*)(ws + L.off_key_range);
     int32_t* key_cost = (int32_t*)(ws + off_key_cost(L));
     plan_rows_kernel<<<(L.n_groups + 3) / 4, 256, 0, stream>>>(q_idx, cu_seqlens_k, d.n_q, d.t_kv, d.n_docs,
-                                                                L.n_groups, row_lo, row_hi, group);
+                                                                L.n_groups, row_lo, row_hi, group, group_real);
     plan_fwd_cost_kernel<<<(L.n_fwd_tiles + 255) / 256, 256, 0, stream>>>(group, L.n_groups, L.n_fwd_tiles,
                                                                           kFwdTileRows / kGroupRows, fwd_cost);
     plan_key_tiles_kernel<<<(L.n_key_tiles + 3) / 4, 256, 0, stream>>>(group, L.n_groups, L.n_key_tiles,
