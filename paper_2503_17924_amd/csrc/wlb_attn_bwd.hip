@@ -32,6 +32,7 @@ struct BwdParams {
     const int32_t* fwd_order; const int32_t* key_order; const int32_t* key_range;
     int n_q, t_kv, hq, hkv, n_groups, n_tiles, n_key_tiles;
     float scale_log2e, scale;
+    int exp_flags;
 };
 
 // ------------------------------------------------------------------------------------------
@@ -612,6 +613,294 @@ __global__ void __launch_bounds__(256) dkv_kernel(const BwdParams p) {
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// dK/dV with role-split wavefronts: one workgroup = 128 keys x one KV head, eight wavefronts.
+// Wavefronts 0-3 ("score" role) hold the K operands of 32 keys each: they compute
+// S = Q K^T, P = exp(scale*S - LSE) (masked), hand P (bf16) to their partner through LDS and
+// accumulate dV^T += dO^T P.  Wavefronts 4-7 ("gradient" role) hold the V operands of the same
+// keys: they compute dP = dO V^T, take P from the partner, form dS = P o (dP - delta) and
+// accumulate dK^T += Q^T dS.  Partners sit on the same SIMD, so each SIMD always has an MFMA
+// stream and a vector-ALU stream to overlap; every wavefront needs about half the registers
+// of an unsplit one, which is what allows two per SIMD.
+// Stages (row group, query head) stream through LDS exactly as in dkv_kernel; per stage:
+//   barrier 1 (tiles landed) -> phase 1 (S,P | dP) -> barrier 2 (P visible) -> phase 2 (dV | dS,dK).
+template <int D>
+__global__ void __launch_bounds__(512) dkv_split_kernel(const BwdParams p) {
+    constexpr int BNK = kBwdKeyTile, GR = kGroupRows, KS = D / 16, DB = D / 32, CPR = D / 8;
+    constexpr int ROWB = D * 2, TILEB = GR * ROWB, NW = 8;
+    static_assert(BNK == 128 && GR == 64, "tiling");
+
+    __shared__ __attribute__((aligned(1024))) char smem[4 * TILEB];          // Q0 | Q1 | dO0 | dO1, swizzled
+    __shared__ __attribute__((aligned(1024))) char pbuf[4 * 2 * 2 * 1024];   // P: [key block][row block][half of 16 rows][lane] x 16 B
+    __shared__ __attribute__((aligned(16))) float lse_s[2][GR];
+    __shared__ __attribute__((aligned(16))) float dl_s[2][GR];
+    __shared__ __attribute__((aligned(16))) int lo_s[2][GR];
+    __shared__ __attribute__((aligned(16))) int hi_s[2][GR];
+
+    const int G = p.hq / p.hkv;
+    const int x = blockIdx.x & 7;
+    const int y = blockIdx.x >> 3;
+    const int hk = y % p.hkv;
+    const int c = y / p.hkv;
+    const int rank = c * 8 + x;
+    if (rank >= p.n_key_tiles) return;
+    const int kt = p.key_order[rank];
+    const int k0 = kt * BNK;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int role = wave >> 2, kblk = wave & 3;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int j16 = lane & 15, gi = (lane >> 4) & 1;
+    const int kw0 = k0 + kblk * 32;
+    const int mykey = kw0 + l32;
+
+    // this wavefront's B operands: K rows (score role) or V rows (gradient role) of its 32 keys
+    bf16x8 bop[KS];
+    {
+        const int kr = min(mykey, p.t_kv - 1);
+        const __bf16* src = (role == 0 ? p.k : p.v) + ((size_t)kr * p.hkv + hk) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) bop[ks] = *reinterpret_cast<const bf16x8*>(src + ks * 16);
+    }
+    f32x16 acc[DB];     // dV^T (score role) or dK^T (gradient role)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+
+    const float cs = p.scale_log2e;
+    const int g_end = p.key_range[2 * kt + 1];
+    const int k1 = min(k0 + BNK, p.t_kv);
+    auto next_group = [&](int g) {
+        for (; g < g_end; ++g) {
+            const int4 gd = reinterpret_cast<const int4*>(p.group)[g];
+            if (gd.y > gd.x && gd.x < k1 && gd.y > k0) break;
+        }
+        return g;
+    };
+
+    const uint32_t q_row = (uint32_t)p.hq * D;
+    const uint32_t q_total = (uint32_t)p.n_q * q_row * 2u;
+    TileDma<D, GR, NW> dma;
+    dma.init(wave, lane, q_row);
+    auto tile_ptr = [&](int which) { return reinterpret_cast<__bf16*>(smem + which * TILEB); };
+    auto issue_stage = [&](int g, int h, int buf) {
+        BufRsrc qrs, ors;
+        qrs.init(p.q + (size_t)h * D, q_total - (uint32_t)h * ROWB);
+        ors.init(p.d_o + (size_t)h * D, q_total - (uint32_t)h * ROWB);
+        dma.issue(qrs, tile_ptr(buf), g * GR, wave);
+        dma.issue(ors, tile_ptr(2 + buf), g * GR, wave);
+    };
+    float r_lse = INFINITY, r_dl = 0.f;
+    int r_lo = kPadLo, r_hi = 0;
+    auto load_small = [&](int g, int h) {
+        if (tid < GR) {
+            const int rowi = g * GR + tid;
+            const bool inr = rowi < p.n_q;
+            const int rc = inr ? rowi : p.n_q - 1;
+            r_hi = inr ? p.row_hi[rc] : 0;
+            const bool real = r_hi > 0;
+            r_lo = real ? p.row_lo[rc] : kPadLo;
+            r_lse = real ? p.lse[(size_t)h * p.n_q + rc] * 1.4426950408889634f : INFINITY;
+            r_dl = real ? p.delta[(size_t)h * p.n_q + rc] : 0.f;
+        }
+    };
+
+    int naddr[KS], taddr[DB][2];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) naddr[ks] = l32 * ROWB + swz<CPR>(l32, ks * 2 + half) * 16;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int qq = t * 8 + half * 4 + (j16 >> 2);
+            const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
+            taddr[db][t] = qq * ROWB + swz<CPR>(qq, dch) * 16 + (j16 & 1) * 8;
+        }
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
+    const uint32_t pbuf_lane = (uint32_t)(uintptr_t)(WLB_LDS char*)pbuf + kblk * 4096 + lane * 16;
+
+    int g = next_group(p.key_range[2 * kt]);
+    int hh = 0, buf = 0;
+    if (g < g_end) {
+        issue_stage(g, hk * G, 0);
+        load_small(g, hk * G);
+    }
+    while (g < g_end) {
+        int gn = g, hn = hh + 1;
+        if (hn == G) { hn = 0; gn = next_group(g + 1); }
+        const int4 gd = reinterpret_cast<const int4*>(p.group)[g];
+        const bool full = (gd.z <= k0) && (k0 + BNK <= gd.w);
+        const bool wave_live = (gd.x < kw0 + 32) && (gd.y > kw0);
+        const bool has_pads = p.group_real[g] < min(GR, p.n_q - g * GR);
+
+        if (tid < GR) { lse_s[buf][tid] = r_lse; dl_s[buf][tid] = r_dl; lo_s[buf][tid] = r_lo; hi_s[buf][tid] = r_hi; }
+        if (!(p.exp_flags & 2)) wait_vmem();
+        __syncthreads();      // barrier 1: stage (g, hh) is in LDS; everyone has left the other buffers and pbuf
+        if (gn < g_end && !(p.exp_flags & 4)) {
+            issue_stage(gn, hk * G + hn, buf ^ 1);
+            load_small(gn, hk * G + hn);
+        }
+        if (has_pads) {
+            const int r = tid >> 3, part = tid & 7;       // 512 threads: 8 per row
+            if (hi_s[buf][r] == 0) {
+                const i32x4 z = {0, 0, 0, 0};
+#pragma unroll
+                for (int i = 0; i < CPR / 8; ++i) {
+                    *reinterpret_cast<i32x4*>(smem + buf * TILEB + r * ROWB + (part * (CPR / 8) + i) * 16) = z;
+                    *reinterpret_cast<i32x4*>(smem + (2 + buf) * TILEB + r * ROWB + (part * (CPR / 8) + i) * 16) = z;
+                }
+            }
+            __syncthreads();
+        }
+        const uint32_t qb_base = smem_base + buf * TILEB, ob_base = smem_base + (2 + buf) * TILEB;
+
+        // ---------------- phase 1
+        bf16x8 pf[2][2];          // score role: P as MFMA B operands, [row block][16-row half]
+        f32x16 dp[2];             // gradient role: dP
+        if (wave_live) {
+            if (role == 0) {
+                // all 16 Q operands are requested before the first MFMA, the two row blocks'
+                // accumulation chains are interleaved
+                bf16x8 qa[2][KS];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                    for (int qb = 0; qb < 2; ++qb)
+                        qa[qb][ks] = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(qb_base + naddr[ks] + qb * 32 * ROWB));
+                f32x16 s2[2];
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s2[qb][r] = 0.f;
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                    for (int qb = 0; qb < 2; ++qb) s2[qb] = mfma32(qa[qb][ks], bop[ks], s2[qb]);
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb) {
+                    const f32x16 s = s2[qb];
+                    float pr[16];
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const int qrow = qb * 32 + r4 * 8 + half * 4;
+                        const f32x4 ls = *reinterpret_cast<const f32x4*>(&lse_s[buf][qrow]);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) pr[r4 * 4 + i] = fast_exp2(fmaf(s[r4 * 4 + i], cs, -ls[i]));
+                        if (!full) {
+                            asm volatile("");   // keep the mask a branch
+                            const i32x4 l4 = *reinterpret_cast<const i32x4*>(&lo_s[buf][qrow]);
+                            const i32x4 h4 = *reinterpret_cast<const i32x4*>(&hi_s[buf][qrow]);
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                pr[r4 * 4 + i] = (mykey >= l4[i] && mykey < h4[i]) ? pr[r4 * 4 + i] : 0.f;
+                        }
+                    }
+#pragma unroll
+                    for (int cc = 0; cc < 2; ++cc) {
+                        pf[qb][cc] = pack8(pr[8 * cc + 0], pr[8 * cc + 1], pr[8 * cc + 2], pr[8 * cc + 3],
+                                           pr[8 * cc + 4], pr[8 * cc + 5], pr[8 * cc + 6], pr[8 * cc + 7]);
+                        *reinterpret_cast<WLB_LDS bf16x8*>((uintptr_t)(pbuf_lane + (qb * 2 + cc) * 1024)) = pf[qb][cc];
+                    }
+                }
+            } else {
+                bf16x8 ga[2][KS];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                    for (int qb = 0; qb < 2; ++qb)
+                        ga[qb][ks] = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(ob_base + naddr[ks] + qb * 32 * ROWB));
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) dp[qb][r] = 0.f;
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                    for (int qb = 0; qb < 2; ++qb) dp[qb] = mfma32(ga[qb][ks], bop[ks], dp[qb]);
+            }
+        }
+        if (!(p.exp_flags & 1)) __syncthreads();      // barrier 2: P of this stage is visible to the partners
+
+        // ---------------- phase 2
+        if (wave_live) {
+            if (role == 0) {
+                // four steps of 16 rows; the transposed dO operands of step i+1 are requested
+                // before the MFMAs of step i are issued
+                bf16x4 tv[2][DB][2];
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) tv[0][db][t] = lds_read_tr4_at(ob_base + taddr[db][t]);
+#pragma unroll
+                for (int st = 0; st < 4; ++st) {
+                    if (st + 1 < 4) {
+#pragma unroll
+                        for (int db = 0; db < DB; ++db)
+#pragma unroll
+                            for (int t = 0; t < 2; ++t)
+                                tv[(st + 1) & 1][db][t] = lds_read_tr4_at(ob_base + taddr[db][t] + (st + 1) * 16 * ROWB);
+                    }
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+                        acc[db] = mfma32(cat4(tv[st & 1][db][0], tv[st & 1][db][1]), pf[st >> 1][st & 1], acc[db]);
+                }
+            } else {
+                bf16x4 tv[2][DB][2];
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) tv[0][db][t] = lds_read_tr4_at(qb_base + taddr[db][t]);
+                bf16x8 dsf[4];
+#pragma unroll
+                for (int st = 0; st < 4; ++st) {
+                    const int qb = st >> 1, cc = st & 1;
+                    const bf16x8 pv = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(pbuf_lane + st * 1024));
+                    float ds[8];
+#pragma unroll
+                    for (int r2 = 0; r2 < 2; ++r2) {
+                        const int qrow = qb * 32 + (cc * 2 + r2) * 8 + half * 4;
+                        const f32x4 dl = *reinterpret_cast<const f32x4*>(&dl_s[buf][qrow]);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            ds[r2 * 4 + i] = (float)pv[r2 * 4 + i] * (dp[qb][cc * 8 + r2 * 4 + i] - dl[i]);
+                    }
+                    dsf[st] = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
+                }
+#pragma unroll
+                for (int st = 0; st < 4; ++st) {
+                    if (st + 1 < 4) {
+#pragma unroll
+                        for (int db = 0; db < DB; ++db)
+#pragma unroll
+                            for (int t = 0; t < 2; ++t)
+                                tv[(st + 1) & 1][db][t] = lds_read_tr4_at(qb_base + taddr[db][t] + (st + 1) * 16 * ROWB);
+                    }
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+                        acc[db] = mfma32(cat4(tv[st & 1][db][0], tv[st & 1][db][1]), dsf[st], acc[db]);
+                }
+            }
+        }
+        g = gn; hh = hn; buf ^= 1;
+    }
+
+    if (mykey < p.t_kv) {
+        __bf16* op = (role == 0 ? p.dv : p.dk) + ((size_t)mykey * p.hkv + hk) * D;
+        const float f = role == 0 ? 1.0f : p.scale;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int d = db * 32 + r4 * 8 + half * 4;
+                *reinterpret_cast<bf16x4*>(op + d) = pack4(acc[db][r4 * 4 + 0] * f, acc[db][r4 * 4 + 1] * f,
+                                                           acc[db][r4 * 4 + 2] * f, acc[db][r4 * 4 + 3] * f);
+            }
+    }
+}
+
 wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const void* q, const void* k,
                       const void* v, const void* o, const float* lse, const void* d_o, void* dq,
                       void* dk, void* dv, char* ws, size_t off_delta, void* stream_) {
@@ -632,6 +921,7 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.n_groups = L.n_groups; p.n_tiles = L.n_fwd_tiles; p.n_key_tiles = L.n_key_tiles;
     p.scale = d.scale;
     p.scale_log2e = d.scale * 1.4426950408889634f;
+    p.exp_flags = getenv("WLB_EXP") ? atoi(getenv("WLB_EXP")) : 0;
 
     const size_t n_lanes = (size_t)d.n_q * d.hq * (d.head_dim / 8);
     const unsigned grid_delta = (unsigned)((n_lanes + 255) / 256);
@@ -640,7 +930,13 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     const bool do_delta = !(d.flags & WLB_ATTN_BWD_SKIP_DELTA);
     const bool do_dq = !(d.flags & WLB_ATTN_BWD_SKIP_DQ);
     const bool do_dkv = !(d.flags & WLB_ATTN_BWD_SKIP_DKV);
-    if (d.head_dim == 128) {
+    static const int dkv_variant = getenv("WLB_DKV_VARIANT") ? atoi(getenv("WLB_DKV_VARIANT")) : 1;
+    if (dkv_variant == 1 && do_dkv) {
+        if (do_delta) { if (d.head_dim == 128) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p); else delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p); }
+        if (do_dq) { if (d.head_dim == 128) dq_pipe_kernel<128><<<grid_dq, 256, 0, stream>>>(p); else dq_pipe_kernel<64><<<grid_dq, 256, 0, stream>>>(p); }
+        if (d.head_dim == 128) dkv_split_kernel<128><<<grid_dkv, 512, 0, stream>>>(p);
+        else dkv_split_kernel<64><<<grid_dkv, 512, 0, stream>>>(p);
+    } else if (d.head_dim == 128) {
         if (do_delta) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p);
         if (do_dq) dq_pipe_kernel<128><<<grid_dq, 256, 0, stream>>>(p);
         if (do_dkv) dkv_kernel<128><<<grid_dkv, 256, 0, stream>>>(p);
