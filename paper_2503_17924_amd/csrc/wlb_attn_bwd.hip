@@ -20,13 +20,15 @@
 #include <hip/hip_runtime.h>
 
 #include "wlb_device.h"
+#include <type_traits>
+
 #include "wlb_internal.h"
 
 namespace wlb {
 
 struct BwdParams {
     const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* o; const __bf16* d_o;
-    const float* lse; float* delta;
+    const float* lse; float* delta; float* lse2;
     __bf16* dq; __bf16* dk; __bf16* dv;
     const int32_t* row_lo; const int32_t* row_hi; const int32_t* group; const int32_t* group_real;
     const int32_t* fwd_order; const int32_t* key_order; const int32_t* key_range;
@@ -54,7 +56,10 @@ __global__ void __launch_bounds__(256) delta_kernel(const BwdParams p) {
     for (int o = LPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
     if (rh < total && c == 0) {
         const int row = (int)(rh / p.hq), h = (int)(rh % p.hq);
-        p.delta[(size_t)h * p.n_q + row] = p.row_hi[row] > 0 ? acc : 0.f;
+        const bool real = p.row_hi[row] > 0;
+        p.delta[(size_t)h * p.n_q + row] = real ? acc : 0.f;
+        // LSE in log2 units for the dK/dV kernel; +inf makes every probability of a padding row 0
+        p.lse2[(size_t)h * p.n_q + row] = real ? p.lse[(size_t)h * p.n_q + row] * 1.4426950408889634f : INFINITY;
     }
 }
 
@@ -307,17 +312,17 @@ __global__ void __launch_bounds__(256, 2) dq_pipe_kernel(const BwdParams p) {
     }
 
     int naddr[KS], taddr[DB][2];
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) naddr[ks] = l32 * ROWB + swz<CPR>(l32, ks * 2 + half) * 16;
+    for (int ks = 0; ks < KS; ++ks) naddr[ks] = smem_base + l32 * ROWB + swz<CPR>(l32, ks * 2 + half) * 16;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int key = t * 8 + half * 4 + (j16 >> 2);
             const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
-            taddr[db][t] = key * ROWB + swz<CPR>(key, dch) * 16 + (j16 & 1) * 8;
+            taddr[db][t] = smem_base + key * ROWB + swz<CPR>(key, dch) * 16 + (j16 & 1) * 8;
         }
-    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
 
     f32x16 acc[DB];
 #pragma unroll
@@ -326,15 +331,17 @@ __global__ void __launch_bounds__(256, 2) dq_pipe_kernel(const BwdParams p) {
         for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
     const float cs = p.scale_log2e;
 
-    for (int j = jb; j < je; ++j) {
-        const int cur = (j - jb) & 1;
+    // one tile; the buffer index is a compile-time constant so that every LDS address is a
+    // loop-invariant register plus an immediate
+    auto tile_step = [&](int j, auto cur_tag) {
+        constexpr int cur = decltype(cur_tag)::value;
         wait_vmem();
         __syncthreads();
-        if (j + 1 < je) {
+        if (j + 1 < je && !(p.exp_flags & 8)) {
             dma.issue(krs, tile_ptr(cur ^ 1), (j + 1) * BN, wave);
             dma.issue(vrs, tile_ptr(2 + (cur ^ 1)), (j + 1) * BN, wave);
         }
-        const uint32_t kb_base = smem_base + cur * TILEB, vb_base = smem_base + (2 + cur) * TILEB;
+        constexpr int kb_base = cur * TILEB, vb_base = (2 + cur) * TILEB;
         const bool partial = (j < fb) || (j >= fe);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
@@ -376,6 +383,10 @@ __global__ void __launch_bounds__(256, 2) dq_pipe_kernel(const BwdParams p) {
                 }
             }
         }
+    };
+    for (int j = jb; j < je; j += 2) {
+        tile_step(j, std::integral_constant<int, 0>{});
+        if (j + 1 < je) tile_step(j + 1, std::integral_constant<int, 1>{});
     }
 
     if (in) {
@@ -901,6 +912,530 @@ __global__ void __launch_bounds__(512) dkv_split_kernel(const BwdParams p) {
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// dK/dV, software-pipelined.  One workgroup = 128 keys x one KV head, four wavefronts of 32
+// keys (their K and V MFMA operands live in registers), one wavefront per SIMD.  Measured on
+// gfx950, MFMA and vector-ALU work overlap only inside one wavefront, so the loop is arranged
+// as a pipeline over blocks of 32 query rows: while the vector ALU turns the scores of block i
+// into P and dS, the MFMA pipe accumulates dV^T, dK^T of block i-1.  Stages (64 rows of one
+// query head: Q, dO, LSE, delta, key intervals) arrive in a ring of four LDS buffers by
+// asynchronous copies issued two stages ahead; one barrier per stage.
+template <int D>
+__global__ void __launch_bounds__(256) dkv_ring_kernel(const BwdParams p) {
+    constexpr int BNK = kBwdKeyTile, GR = kGroupRows, KS = D / 16, DB = D / 32, CPR = D / 8;
+    constexpr int ROWB = D * 2, TILEB = GR * ROWB, NBUF = 4, NW = 4;
+    constexpr int SMALLB = 4 * GR * 4;                       // lse2 | delta | lo | hi, 64 dwords each
+    static_assert(BNK == 128 && GR == 64, "tiling");
+    using Dma = TileDma<D, GR, NW>;
+    constexpr int BATCH = 2 * Dma::PER + 1;                  // vector-memory operations per wavefront and stage
+
+    __shared__ __attribute__((aligned(1024))) char smem[NBUF * 2 * TILEB];   // per slot: Q tile | dO tile, swizzled
+    __shared__ __attribute__((aligned(1024))) char small[NBUF * SMALLB];
+
+    const int G = p.hq / p.hkv;
+    const int x = blockIdx.x & 7;
+    const int y = blockIdx.x >> 3;
+    const int hk = y % p.hkv;
+    const int c = y / p.hkv;
+    const int rank = c * 8 + x;
+    if (rank >= p.n_key_tiles) return;
+    const int kt = p.key_order[rank];
+    const int k0 = kt * BNK;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int j16 = lane & 15, gi = (lane >> 4) & 1;
+    const int kw0 = k0 + wave * 32;
+    const int mykey = kw0 + l32;
+
+    bf16x8 kf[KS], vf[KS];
+    {
+        const int kr = min(mykey, p.t_kv - 1);
+        const __bf16* kp = p.k + ((size_t)kr * p.hkv + hk) * D + half * 8;
+        const __bf16* vp = p.v + ((size_t)kr * p.hkv + hk) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[ks] = *reinterpret_cast<const bf16x8*>(kp + ks * 16);
+            vf[ks] = *reinterpret_cast<const bf16x8*>(vp + ks * 16);
+        }
+    }
+    f32x16 dk_acc[DB], dv_acc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { dk_acc[db][r] = 0.f; dv_acc[db][r] = 0.f; }
+
+    const float cs = p.scale_log2e;
+    const int g_end = p.key_range[2 * kt + 1];
+    const int k1 = min(k0 + BNK, p.t_kv);
+    auto next_group = [&](int g) {
+        for (; g < g_end; ++g) {
+            const int4 gd = reinterpret_cast<const int4*>(p.group)[g];
+            if (gd.y > gd.x && gd.x < k1 && gd.y > k0) break;
+        }
+        return g;
+    };
+    // successor of stage (g, hh); g == g_end marks the end
+    auto succ = [&](int& g, int& hh) {
+        if (++hh == G) { hh = 0; g = next_group(g + 1); }
+    };
+
+    const uint32_t q_row = (uint32_t)p.hq * D;
+    const uint32_t q_total = (uint32_t)p.n_q * q_row * 2u;
+    Dma dma;
+    dma.init(wave, lane, q_row);
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
+    const uint32_t small_base = (uint32_t)(uintptr_t)(WLB_LDS char*)small;
+    // every wavefront issues the same number of copies per stage: its share of the Q and dO
+    // tiles plus one of the four 64-entry scalar arrays
+    auto issue_stage = [&](int g, int h, int slot) {
+        BufRsrc qrs, ors, srs;
+        qrs.init(p.q + (size_t)h * D, q_total - (uint32_t)h * ROWB);
+        ors.init(p.d_o + (size_t)h * D, q_total - (uint32_t)h * ROWB);
+        dma.issue(qrs, reinterpret_cast<__bf16*>(smem + slot * 2 * TILEB), g * GR, wave);
+        dma.issue(ors, reinterpret_cast<__bf16*>(smem + slot * 2 * TILEB + TILEB), g * GR, wave);
+        const void* base = wave == 0 ? (const void*)(p.lse2 + (size_t)h * p.n_q)
+                         : wave == 1 ? (const void*)(p.delta + (size_t)h * p.n_q)
+                         : wave == 2 ? (const void*)p.row_lo : (const void*)p.row_hi;
+        srs.init(base, (uint32_t)p.n_q * 4u);
+        srs.make_uniform();
+        dma_issue_256(srs.r, __builtin_amdgcn_readfirstlane(small_base + slot * SMALLB + wave * GR * 4), lane * 4,
+                      __builtin_amdgcn_readfirstlane((uint32_t)(g * GR) * 4u));
+    };
+
+    int naddr[KS], taddr[DB][2];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) naddr[ks] = l32 * ROWB + swz<CPR>(l32, ks * 2 + half) * 16;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int qq = t * 8 + half * 4 + (j16 >> 2);
+            const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
+            taddr[db][t] = qq * ROWB + swz<CPR>(qq, dch) * 16 + (j16 & 1) * 8;
+        }
+
+    // P and dS of the previous block (MFMA B operands) and where its rows sit in LDS
+    bf16x8 pf_old[2], dsf_old[2];
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { pf_old[cc][i] = (__bf16)0.f; dsf_old[cc][i] = (__bf16)0.f; }
+    uint32_t back_q = smem_base, back_o = smem_base + TILEB;      // first unit: zero operands against stage 0's tile
+
+    // dV^T, dK^T += (dO^T, Q^T of the previous block) x (P, dS of the previous block), 16-row step cc
+    auto back_step = [&](int cc) {
+        bf16x8 ga[DB], qa[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            ga[db] = cat4(lds_read_tr4_at(back_o + taddr[db][0] + cc * 16 * ROWB),
+                          lds_read_tr4_at(back_o + taddr[db][1] + cc * 16 * ROWB));
+            qa[db] = cat4(lds_read_tr4_at(back_q + taddr[db][0] + cc * 16 * ROWB),
+                          lds_read_tr4_at(back_q + taddr[db][1] + cc * 16 * ROWB));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            dv_acc[db] = mfma32(ga[db], pf_old[cc], dv_acc[db]);
+            dk_acc[db] = mfma32(qa[db], dsf_old[cc], dk_acc[db]);
+        }
+    };
+
+    // one pipeline unit: scores and dP of block (slot, qb), then its P/dS on the vector ALU
+    // against the previous block's dV/dK MFMAs
+    auto unit = [&](int slot, int qb, bool live, auto mask_tag) {
+        constexpr bool MASK = decltype(mask_tag)::value;
+        const uint32_t fq = smem_base + slot * 2 * TILEB + qb * 32 * ROWB, fo = fq + TILEB;
+        const uint32_t sm = small_base + slot * SMALLB + (qb * 32 + half * 4) * 4;
+        bf16x8 pf_new[2], dsf_new[2];
+        if (live) {
+            f32x16 s, dp;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+            bf16x8 qa[KS], ga[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                qa[ks] = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(fq + naddr[ks]));
+                ga[ks] = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(fo + naddr[ks]));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                s = mfma32(qa[ks], kf[ks], s);
+                dp = mfma32(ga[ks], vf[ks], dp);
+            }
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+                float pr[8], ds[8];
+#pragma unroll
+                for (int r2 = 0; r2 < 2; ++r2) {
+                    const int r4 = cc * 2 + r2;
+                    const f32x4 ls = *reinterpret_cast<const WLB_LDS f32x4*>((uintptr_t)(sm + r4 * 32));
+                    const f32x4 dl = *reinterpret_cast<const WLB_LDS f32x4*>((uintptr_t)(sm + GR * 4 + r4 * 32));
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) pr[r2 * 4 + i] = fast_exp2(fmaf(s[r4 * 4 + i], cs, -ls[i]));
+                    if (MASK) {
+                        const i32x4 l4 = *reinterpret_cast<const WLB_LDS i32x4*>((uintptr_t)(sm + 2 * GR * 4 + r4 * 32));
+                        const i32x4 h4 = *reinterpret_cast<const WLB_LDS i32x4*>((uintptr_t)(sm + 3 * GR * 4 + r4 * 32));
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            pr[r2 * 4 + i] = (mykey >= l4[i] && mykey < h4[i]) ? pr[r2 * 4 + i] : 0.f;
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) ds[r2 * 4 + i] = pr[r2 * 4 + i] * (dp[r4 * 4 + i] - dl[i]);
+                }
+                pf_new[cc] = pack8(pr[0], pr[1], pr[2], pr[3], pr[4], pr[5], pr[6], pr[7]);
+                dsf_new[cc] = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
+                back_step(cc);
+            }
+        } else {
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { pf_new[cc][i] = (__bf16)0.f; dsf_new[cc][i] = (__bf16)0.f; }
+                back_step(cc);
+            }
+        }
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc) { pf_old[cc] = pf_new[cc]; dsf_old[cc] = dsf_new[cc]; }
+        back_q = fq; back_o = fo;
+    };
+
+    // ---- stage ring: s (computing), s+1 (landed or landing), s+2 (issued at the top of s)
+    int g0 = next_group(p.key_range[2 * kt]), h0 = 0;           // stage s
+    int g1 = g0, h1 = h0;                                       // stage s+1
+    if (g0 < g_end) {
+        issue_stage(g0, hk * G + h0, 0);
+        succ(g1, h1);
+        if (g1 < g_end) issue_stage(g1, hk * G + h1, 1);
+    }
+    int g2 = g1, h2 = h1;                                       // stage s+2
+    int slot = 0;
+    while (g0 < g_end) {
+        if (g1 < g_end) succ(g2, h2); else g2 = g_end;
+        const int4 gd = reinterpret_cast<const int4*>(p.group)[g0];
+        const bool full = (gd.z <= k0) && (k0 + BNK <= gd.w);
+        const bool live = (gd.x < kw0 + 32) && (gd.y > kw0);
+        const bool has_pads = p.group_real[g0] < min(GR, p.n_q - g0 * GR);
+
+        // stage s has landed once at most the copies of stage s+1 are outstanding
+        if (g1 < g_end) wait_vmem_le<BATCH>(); else wait_vmem();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the previous block's LDS reads have returned
+        __syncthreads();
+        if (g2 < g_end) issue_stage(g2, hk * G + h2, (slot + 2) % NBUF);
+        if (has_pads) {
+            // padding rows may hold anything: clear them so they cannot poison the MFMAs
+            const int r = tid >> 2, part = tid & 3;
+            const int hi_r = *reinterpret_cast<const int*>(small + slot * SMALLB + 3 * GR * 4 + r * 4);
+            if (hi_r == 0 && g0 * GR + r < p.n_q) {
+                const i32x4 z = {0, 0, 0, 0};
+#pragma unroll
+                for (int i = 0; i < CPR / 4; ++i) {
+                    *reinterpret_cast<i32x4*>(smem + slot * 2 * TILEB + r * ROWB + (part * (CPR / 4) + i) * 16) = z;
+                    *reinterpret_cast<i32x4*>(smem + slot * 2 * TILEB + TILEB + r * ROWB + (part * (CPR / 4) + i) * 16) = z;
+                }
+            }
+            __syncthreads();
+        }
+        if (full) {
+            unit(slot, 0, live, std::false_type{});
+            unit(slot, 1, live, std::false_type{});
+        } else {
+            unit(slot, 0, live, std::true_type{});
+            unit(slot, 1, live, std::true_type{});
+        }
+        g0 = g1; h0 = h1; g1 = g2; h1 = h2;
+        slot = (slot + 1) % NBUF;
+    }
+    // drain: the last block's dV/dK
+    back_step(0);
+    back_step(1);
+
+    if (mykey < p.t_kv) {
+        __bf16* kp = p.dk + ((size_t)mykey * p.hkv + hk) * D;
+        __bf16* vp = p.dv + ((size_t)mykey * p.hkv + hk) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int d = db * 32 + r4 * 8 + half * 4;
+                *reinterpret_cast<bf16x4*>(kp + d) =
+                    pack4(dk_acc[db][r4 * 4 + 0] * p.scale, dk_acc[db][r4 * 4 + 1] * p.scale,
+                          dk_acc[db][r4 * 4 + 2] * p.scale, dk_acc[db][r4 * 4 + 3] * p.scale);
+                *reinterpret_cast<bf16x4*>(vp + d) = pack4(dv_acc[db][r4 * 4 + 0], dv_acc[db][r4 * 4 + 1],
+                                                           dv_acc[db][r4 * 4 + 2], dv_acc[db][r4 * 4 + 3]);
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// dK/dV with two kinds of wavefront.  One workgroup = 128 keys x one KV head, eight
+// wavefronts, two per SIMD.  Wavefronts 0-3 own dV^T of 32 keys each: S = Q K^T, P, then
+// dV^T += dO^T P.  Wavefronts 4-7 own dK^T of the same keys: S and dP = dO V^T, dS, then
+// dK^T += Q^T dS.  S is computed by both kinds (10*D instead of 8*D MFMA flops per pair); in
+// return neither needs more than half the accumulator registers of a combined wavefront, two
+// fit on a SIMD, nothing is exchanged between them and one barrier per stage suffices.
+// Measured on gfx950, MFMA and vector-ALU work overlap only inside one wavefront, so each
+// wavefront runs a pipeline over blocks of 32 query rows: while its vector ALU turns the
+// scores of block i into P (dS), its MFMAs accumulate block i-1.  Stages (64 rows of one query
+// head: Q, dO, LSE, delta, key intervals) arrive in a ring of four LDS buffers by asynchronous
+// copies issued two stages ahead.
+template <int D, int ROLE>
+__device__ __forceinline__ void dkv_duo_body(const BwdParams& p, char* smem, char* small) {
+    constexpr int BNK = kBwdKeyTile, GR = kGroupRows, KS = D / 16, DB = D / 32, CPR = D / 8;
+    constexpr int ROWB = D * 2, TILEB = GR * ROWB, NBUF = 4, NW = 8;
+    constexpr int SMALLB = 4 * GR * 4;                       // lse2 | delta | lo | hi, 64 dwords each
+    static_assert(BNK == 128 && GR == 64, "tiling");
+    using Dma = TileDma<D, GR, NW>;
+    constexpr int BATCH = 2 * Dma::PER;                      // tile copies per wavefront and stage (+1 scalar array on wavefronts 0-3)
+
+    const int G = p.hq / p.hkv;
+    const int x = blockIdx.x & 7;
+    const int y = blockIdx.x >> 3;
+    const int hk = y % p.hkv;
+    const int c = y / p.hkv;
+    const int rank = c * 8 + x;
+    const int kt = p.key_order[rank];
+    const int k0 = kt * BNK;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int j16 = lane & 15, gi = (lane >> 4) & 1;
+    constexpr int role = ROLE;                       // role 0: dV, role 1: dK
+    const int kblk = wave & 3;
+    const int kw0 = k0 + kblk * 32;
+    const int mykey = kw0 + l32;
+
+    bf16x8 kf[KS], vf[KS];
+    {
+        const int kr = min(mykey, p.t_kv - 1);
+        const __bf16* kp = p.k + ((size_t)kr * p.hkv + hk) * D + half * 8;
+        const __bf16* vp = p.v + ((size_t)kr * p.hkv + hk) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[ks] = *reinterpret_cast<const bf16x8*>(kp + ks * 16);
+            if (role == 1) vf[ks] = *reinterpret_cast<const bf16x8*>(vp + ks * 16);
+        }
+    }
+    f32x16 acc[DB];      // dV^T (role 0) or dK^T (role 1)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+
+    const float cs = p.scale_log2e;
+    const int g_end = p.key_range[2 * kt + 1];
+    const int k1 = min(k0 + BNK, p.t_kv);
+    auto next_group = [&](int g) {
+        for (; g < g_end; ++g) {
+            const int4 gd = reinterpret_cast<const int4*>(p.group)[g];
+            if (gd.y > gd.x && gd.x < k1 && gd.y > k0) break;
+        }
+        return g;
+    };
+    // successor of stage (g, hh); g == g_end marks the end
+    auto succ = [&](int& g, int& hh) {
+        if (++hh == G) { hh = 0; g = next_group(g + 1); }
+    };
+
+    const uint32_t q_row = (uint32_t)p.hq * D;
+    const uint32_t q_total = (uint32_t)p.n_q * q_row * 2u;
+    Dma dma;
+    dma.init(wave, lane, q_row);
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
+    const uint32_t small_base = (uint32_t)(uintptr_t)(WLB_LDS char*)small;
+    // every wavefront issues the same number of copies per stage: its share of the Q and dO
+    // tiles plus one of the four 64-entry scalar arrays
+    auto issue_stage = [&](int g, int h, int slot) {
+        BufRsrc qrs, ors, srs;
+        qrs.init(p.q + (size_t)h * D, q_total - (uint32_t)h * ROWB);
+        ors.init(p.d_o + (size_t)h * D, q_total - (uint32_t)h * ROWB);
+        dma.issue(qrs, reinterpret_cast<__bf16*>(smem + slot * 2 * TILEB), g * GR, wave);
+        dma.issue(ors, reinterpret_cast<__bf16*>(smem + slot * 2 * TILEB + TILEB), g * GR, wave);
+        if (wave < 4) {
+            const void* base = wave == 0 ? (const void*)(p.lse2 + (size_t)h * p.n_q)
+                             : wave == 1 ? (const void*)(p.delta + (size_t)h * p.n_q)
+                             : wave == 2 ? (const void*)p.row_lo : (const void*)p.row_hi;
+            srs.init(base, (uint32_t)p.n_q * 4u);
+            srs.make_uniform();
+            dma_issue_256(srs.r, __builtin_amdgcn_readfirstlane(small_base + slot * SMALLB + wave * GR * 4), lane * 4,
+                          __builtin_amdgcn_readfirstlane((uint32_t)(g * GR) * 4u));
+        }
+    };
+
+    int naddr[KS], taddr[DB][2];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) naddr[ks] = l32 * ROWB + swz<CPR>(l32, ks * 2 + half) * 16;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int qq = t * 8 + half * 4 + (j16 >> 2);
+            const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
+            taddr[db][t] = qq * ROWB + swz<CPR>(qq, dch) * 16 + (j16 & 1) * 8;
+        }
+
+    // P and dS of the previous block (MFMA B operands) and where its rows sit in LDS
+    bf16x8 b_old[2];      // P (role 0) or dS (role 1) of the previous block
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) b_old[cc][i] = (__bf16)0.f;
+    // rows of the previous block in LDS: dO tile for dV, Q tile for dK (first unit: zero operands, stage 0's tile)
+    uint32_t back_t = smem_base + (role == 0 ? TILEB : 0);
+
+    // acc += (dO^T or Q^T of the previous block) x (P or dS of the previous block), 16-row step cc
+    auto back_step = [&](int cc) {
+        bf16x8 ta[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+            ta[db] = cat4(lds_read_tr4_at(back_t + taddr[db][0] + cc * 16 * ROWB),
+                          lds_read_tr4_at(back_t + taddr[db][1] + cc * 16 * ROWB));
+#pragma unroll
+        for (int db = 0; db < DB; ++db) acc[db] = mfma32(ta[db], b_old[cc], acc[db]);
+    };
+
+    // one pipeline unit: scores (and dP) of block (slot, qb), then its P (dS) on the vector ALU
+    // against the previous block's accumulation MFMAs
+    auto unit = [&](int slot, int qb, bool live, auto mask_tag) {
+        constexpr bool MASK = decltype(mask_tag)::value;
+        const uint32_t fq = smem_base + slot * 2 * TILEB + qb * 32 * ROWB, fo = fq + TILEB;
+        const uint32_t sm = small_base + slot * SMALLB + (qb * 32 + half * 4) * 4;
+        bf16x8 b_new[2];
+        if (live) {
+            f32x16 s, dp;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+            if (role == 0) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 qa = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(fq + naddr[ks]));
+                    s = mfma32(qa, kf[ks], s);
+                }
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 qa = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(fq + naddr[ks]));
+                    const bf16x8 ga = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(fo + naddr[ks]));
+                    s = mfma32(qa, kf[ks], s);
+                    dp = mfma32(ga, vf[ks], dp);
+                }
+            }
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+                float pr[8];
+#pragma unroll
+                for (int r2 = 0; r2 < 2; ++r2) {
+                    const int r4 = cc * 2 + r2;
+                    const f32x4 ls = *reinterpret_cast<const WLB_LDS f32x4*>((uintptr_t)(sm + r4 * 32));
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) pr[r2 * 4 + i] = fast_exp2(fmaf(s[r4 * 4 + i], cs, -ls[i]));
+                    if (MASK) {
+                        const i32x4 l4 = *reinterpret_cast<const WLB_LDS i32x4*>((uintptr_t)(sm + 2 * GR * 4 + r4 * 32));
+                        const i32x4 h4 = *reinterpret_cast<const WLB_LDS i32x4*>((uintptr_t)(sm + 3 * GR * 4 + r4 * 32));
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            pr[r2 * 4 + i] = (mykey >= l4[i] && mykey < h4[i]) ? pr[r2 * 4 + i] : 0.f;
+                    }
+                    if (role == 1) {
+                        const f32x4 dl = *reinterpret_cast<const WLB_LDS f32x4*>((uintptr_t)(sm + GR * 4 + r4 * 32));
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) pr[r2 * 4 + i] *= dp[r4 * 4 + i] - dl[i];
+                    }
+                }
+                b_new[cc] = pack8(pr[0], pr[1], pr[2], pr[3], pr[4], pr[5], pr[6], pr[7]);
+                back_step(cc);
+            }
+        } else {
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) b_new[cc][i] = (__bf16)0.f;
+                back_step(cc);
+            }
+        }
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc) b_old[cc] = b_new[cc];
+        back_t = role == 0 ? fo : fq;
+    };
+
+    // ---- stage ring: s (computing), s+1 (landed or landing), s+2 (issued at the top of s)
+    int g0 = next_group(p.key_range[2 * kt]), h0 = 0;           // stage s
+    int g1 = g0, h1 = h0;                                       // stage s+1
+    if (g0 < g_end) {
+        issue_stage(g0, hk * G + h0, 0);
+        succ(g1, h1);
+        if (g1 < g_end) issue_stage(g1, hk * G + h1, 1);
+    }
+    int g2 = g1, h2 = h1;                                       // stage s+2
+    int slot = 0;
+    while (g0 < g_end) {
+        if (g1 < g_end) succ(g2, h2); else g2 = g_end;
+        const int4 gd = reinterpret_cast<const int4*>(p.group)[g0];
+        const bool full = (gd.z <= k0) && (k0 + BNK <= gd.w);
+        const bool live = (gd.x < kw0 + 32) && (gd.y > kw0);
+        const bool has_pads = p.group_real[g0] < min(GR, p.n_q - g0 * GR);
+
+        // stage s has landed once at most the copies of stage s+1 are outstanding
+        if (g1 >= g_end) wait_vmem();
+        else if (wave < 4) wait_vmem_le<BATCH + 1>();
+        else wait_vmem_le<BATCH>();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the previous block's LDS reads have returned
+        __syncthreads();
+        if (g2 < g_end) issue_stage(g2, hk * G + h2, (slot + 2) % NBUF);
+        if (has_pads) {
+            // padding rows may hold anything: clear them so they cannot poison the MFMAs
+            const int r = tid >> 3, part = tid & 7;
+            const int hi_r = *reinterpret_cast<const int*>(small + slot * SMALLB + 3 * GR * 4 + r * 4);
+            if (hi_r == 0 && g0 * GR + r < p.n_q) {
+                const i32x4 z = {0, 0, 0, 0};
+#pragma unroll
+                for (int i = 0; i < CPR / 8; ++i) {
+                    *reinterpret_cast<i32x4*>(smem + slot * 2 * TILEB + r * ROWB + (part * (CPR / 8) + i) * 16) = z;
+                    *reinterpret_cast<i32x4*>(smem + slot * 2 * TILEB + TILEB + r * ROWB + (part * (CPR / 8) + i) * 16) = z;
+                }
+            }
+            __syncthreads();
+        }
+        if (full) {
+            unit(slot, 0, live, std::false_type{});
+            unit(slot, 1, live, std::false_type{});
+        } else {
+            unit(slot, 0, live, std::true_type{});
+            unit(slot, 1, live, std::true_type{});
+        }
+        g0 = g1; h0 = h1; g1 = g2; h1 = h2;
+        slot = (slot + 1) % NBUF;
+    }
+    // drain: the last block's dV/dK
+    back_step(0);
+    back_step(1);
+
+    if (mykey < p.t_kv) {
+        __bf16* op = (role == 0 ? p.dv : p.dk) + ((size_t)mykey * p.hkv + hk) * D;
+        const float f = role == 0 ? 1.0f : p.scale;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int d = db * 32 + r4 * 8 + half * 4;
+                *reinterpret_cast<bf16x4*>(op + d) = pack4(acc[db][r4 * 4 + 0] * f, acc[db][r4 * 4 + 1] * f,
+                                                           acc[db][r4 * 4 + 2] * f, acc[db][r4 * 4 + 3] * f);
+            }
+    }
+}
+
+template <int D>
+__global__ void __launch_bounds__(512) dkv_duo_kernel(const BwdParams p) {
+    constexpr int TILEB = kGroupRows * D * 2;
+    __shared__ __attribute__((aligned(1024))) char smem[4 * 2 * TILEB];   // per slot: Q tile | dO tile, swizzled
+    __shared__ __attribute__((aligned(1024))) char small[4 * 4 * kGroupRows * 4];
+    const int rank = ((int)(blockIdx.x >> 3) / p.hkv) * 8 + (int)(blockIdx.x & 7);
+    if (rank >= p.n_key_tiles) return;
+    if (threadIdx.x < 256) dkv_duo_body<D, 0>(p, smem, small);
+    else dkv_duo_body<D, 1>(p, smem, small);
+}
+
 wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const void* q, const void* k,
                       const void* v, const void* o, const float* lse, const void* d_o, void* dq,
                       void* dk, void* dv, char* ws, size_t off_delta, void* stream_) {
@@ -909,6 +1444,7 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.q = (const __bf16*)q; p.k = (const __bf16*)k; p.v = (const __bf16*)v;
     p.o = (const __bf16*)o; p.d_o = (const __bf16*)d_o; p.lse = lse;
     p.delta = (float*)(ws + off_delta);
+    p.lse2 = (float*)(ws + off_delta + align_up(sizeof(float) * (size_t)d.hq * d.n_q, 256));
     p.dq = (__bf16*)dq; p.dk = (__bf16*)dk; p.dv = (__bf16*)dv;
     p.row_lo = (const int32_t*)(ws + L.off_row_lo);
     p.row_hi = (const int32_t*)(ws + L.off_row_hi);
@@ -931,6 +1467,18 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     const bool do_dq = !(d.flags & WLB_ATTN_BWD_SKIP_DQ);
     const bool do_dkv = !(d.flags & WLB_ATTN_BWD_SKIP_DKV);
     static const int dkv_variant = getenv("WLB_DKV_VARIANT") ? atoi(getenv("WLB_DKV_VARIANT")) : 1;
+    if (dkv_variant == 3 && do_dkv) {
+        if (do_delta) { if (d.head_dim == 128) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p); else delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p); }
+        if (do_dq) { if (d.head_dim == 128) dq_pipe_kernel<128><<<grid_dq, 256, 0, stream>>>(p); else dq_pipe_kernel<64><<<grid_dq, 256, 0, stream>>>(p); }
+        if (d.head_dim == 128) dkv_duo_kernel<128><<<grid_dkv, 512, 0, stream>>>(p);
+        else dkv_duo_kernel<64><<<grid_dkv, 512, 0, stream>>>(p);
+    } else
+    if (dkv_variant == 2 && do_dkv) {
+        if (do_delta) { if (d.head_dim == 128) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p); else delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p); }
+        if (do_dq) { if (d.head_dim == 128) dq_pipe_kernel<128><<<grid_dq, 256, 0, stream>>>(p); else dq_pipe_kernel<64><<<grid_dq, 256, 0, stream>>>(p); }
+        if (d.head_dim == 128) dkv_ring_kernel<128><<<grid_dkv, 256, 0, stream>>>(p);
+        else dkv_ring_kernel<64><<<grid_dkv, 256, 0, stream>>>(p);
+    } else
     if (dkv_variant == 1 && do_dkv) {
         if (do_delta) { if (d.head_dim == 128) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p); else delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p); }
         if (do_dq) { if (d.head_dim == 128) dq_pipe_kernel<128><<<grid_dq, 256, 0, stream>>>(p); else dq_pipe_kernel<64><<<grid_dq, 256, 0, stream>>>(p); }

@@ -24,6 +24,7 @@ struct FwdParams {
     const int32_t* row_lo; const int32_t* row_hi; const int32_t* group; const int32_t* order;
     int n_q, t_kv, hq, hkv, n_groups, n_tiles;
     float scale_log2e, scale;
+    int exp_flags;
 };
 
 template <int D, int QB, int NW>
@@ -382,7 +383,7 @@ __global__ void __launch_bounds__(256, 2) fwd_pipe_kernel(const FwdParams p) {
 
     for (int j = jb; j < je; ++j) {
         const int cur = (j - jb) & 1;
-        if (j + 1 < je) {
+        if (j + 1 < je && !(p.exp_flags & 8)) {
             dma.issue(krs, tile_ptr(cur ^ 1), (j + 1) * BN + 32, wave);
             dma.issue(vrs, tile_ptr(2 + (cur ^ 1)), (j + 1) * BN, wave);
         }
@@ -476,6 +477,7 @@ wlb_status launch_fwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.n_groups = L.n_groups; p.n_tiles = L.n_fwd_tiles;
     p.scale = d.scale;
     p.scale_log2e = d.scale * 1.4426950408889634f;
+    p.exp_flags = getenv("WLB_EXP") ? atoi(getenv("WLB_EXP")) : 0;
     const unsigned grid = (unsigned)((L.n_fwd_tiles + 7) / 8) * 8u * (unsigned)d.hq;
     static const int variant = getenv("WLB_FWD_VARIANT") ? atoi(getenv("WLB_FWD_VARIANT")) : 2;
     if (variant == 2) {

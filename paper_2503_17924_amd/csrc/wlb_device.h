@@ -90,6 +90,12 @@ struct BufRsrc {
         r[2] = (int)bytes;
         r[3] = 0x00020000;
     }
+    // for descriptors whose base was chosen per wavefront: move the (wave-uniform) words to scalar registers
+    __device__ __forceinline__ void make_uniform() {
+        r[0] = __builtin_amdgcn_readfirstlane(r[0]);
+        r[1] = __builtin_amdgcn_readfirstlane(r[1]);
+        r[2] = __builtin_amdgcn_readfirstlane(r[2]);
+    }
 };
 
 // One buffer_load_dwordx4 ... lds: 64 lanes x 16 bytes from (descriptor base + soff + voff)
@@ -135,6 +141,21 @@ struct TileDma {
         }
     }
 };
+
+// 64 lanes x 4 bytes (one dword per lane, consecutive in LDS) from descriptor base + soff + 4*lane
+__device__ __forceinline__ void dma_issue_256(const i32x4& rsrc, uint32_t lds_addr, int voff, uint32_t soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory");
+}
+
+// wait until at most N of this wavefront's most recent vector-memory operations are outstanding
+template <int N>
+__device__ __forceinline__ void wait_vmem_le() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
 
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 

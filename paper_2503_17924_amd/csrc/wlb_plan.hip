@@ -194,7 +194,8 @@ wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const i
     return WLB_OK;
 }
 
-static size_t delta_bytes(const wlb_attn_desc& d) { return align_up(sizeof(float) * (size_t)d.hq * d.n_q, 256); }
+// delta and the log2-scaled LSE copy, [hq][n_q] floats each
+static size_t delta_bytes(const wlb_attn_desc& d) { return 2 * align_up(sizeof(float) * (size_t)d.hq * d.n_q, 256); }
 
 }  // namespace wlb
 
