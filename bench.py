@@ -26,6 +26,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 COST_A, COST_B = 6, 640000    # packer cost model, picoseconds per token^2 / per token
+# HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size), measured with
+# rocprofv3 --pmc on this workload: profiles/hbm_traffic_c2_128k_cp8.txt
+MEASURED_TRAFFIC_BYTES = {("c2_128k_cp8", "dkv_kernel"): int((4.627 + 0.066) * 2**30),
+                          ("c2_128k_cp8", "dq_kernel"): int((1.105 + 0.031) * 2**30),
+                          ("c2_128k_cp8", "fwd_kernel"): int((1.110 + 0.032) * 2**30)}
 
 
 def parse():
@@ -36,6 +41,8 @@ def parse():
     ap.add_argument("--config", type=int, default=2, help="workload index (2 = the 128K CP=8 config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-seq", action="store_true", help="skip the per-sequence sharding comparison")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device copy (reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -111,6 +118,13 @@ def main():
                 e2.record()
                 record.append((e0, e1, e2))
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=device)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     main_states = ranks[B.SHARD_PER_DOC_PADDED]
     for _ in range(args.warmup):
         step(main_states)
@@ -148,10 +162,9 @@ def main():
             "bwd_ms": [round(x, 3) for x in lat[:, 1]],
             "pairs_max_over_mean": float(max(s.pairs for s in ranks[m]) / np.mean([s.pairs for s in ranks[m]]))}
 
-    # ---- per-kernel timing on rank 0 (the library's measurement flags isolate each kernel)
-    st = main_states[0]
-
-    def time_call(fn, reps=5):
+    # ---- per-kernel timing on every rank (the library's measurement flags isolate each kernel);
+    # HIP events on the stream the library launches on (torch's current stream)
+    def time_call(fn, reps=3):
         fn()
         torch.cuda.synchronize()
         ts = []
@@ -165,25 +178,33 @@ def main():
         return float(np.mean(ts))
 
     kern = {}
-    kern["plan_ms"] = time_call(lambda: st.attn.plan())
-    kern["fwd_ms"] = time_call(lambda: st.attn.forward(st.q, full["k"], full["v"], st.o, st.lse))
-    if w.backward:
-        bw = lambda fl: st.attn.backward(st.q, full["k"], full["v"], st.o, st.lse, st.do, st.dq, st.dk, st.dv,
-                                         extra_flags=fl)
-        kern["delta_ms"] = time_call(lambda: bw(B.ATTN_BWD_SKIP_DQ | B.ATTN_BWD_SKIP_DKV))
-        kern["dq_ms"] = time_call(lambda: bw(B.ATTN_BWD_SKIP_DELTA | B.ATTN_BWD_SKIP_DKV))
-        kern["dkv_ms"] = time_call(lambda: bw(B.ATTN_BWD_SKIP_DELTA | B.ATTN_BWD_SKIP_DQ))
-    # algorithmic flops per launch: forward 4*D per pair and head; the dK/dV kernel carries the
-    # score and dP recomputation plus dK and dV (8*D); the dQ kernel adds dQ (2*D)
-    p0 = st.pairs
+
+    def add(name, ms):
+        kern.setdefault(name, []).append(ms)
+
+    for st in main_states:
+        add("plan_ms", time_call(lambda: st.attn.plan()))
+        add("fwd_ms", time_call(lambda: st.attn.forward(st.q, full["k"], full["v"], st.o, st.lse)))
+        if w.backward:
+            bw = lambda fl: st.attn.backward(st.q, full["k"], full["v"], st.o, st.lse, st.do, st.dq, st.dk, st.dv,
+                                             extra_flags=fl)
+            add("delta_ms", time_call(lambda: bw(B.ATTN_BWD_SKIP_DQ | B.ATTN_BWD_SKIP_DKV)))
+            add("dq_ms", time_call(lambda: bw(B.ATTN_BWD_SKIP_DELTA | B.ATTN_BWD_SKIP_DKV)))
+            add("dkv_ms", time_call(lambda: bw(B.ATTN_BWD_SKIP_DELTA | B.ATTN_BWD_SKIP_DQ)))
+    kern = {k: float(np.mean(v)) for k, v in kern.items()}
+    # algorithmic flops per launch (mean over ranks): forward 4*D per pair and head; the dK/dV
+    # kernel carries the score and dP recomputation plus dK and dV (8*D); the dQ kernel adds dQ (2*D)
+    p0 = float(np.mean([st.pairs for st in main_states]))
     alg = {"fwd": 4.0 * D * hq * p0, "dkv": 8.0 * D * hq * p0, "dq": 2.0 * D * hq * p0}
     tfl = {k: alg[k] / (kern[k + "_ms"] * 1e-3) / 1e12 for k in alg if k + "_ms" in kern}
     dominant = max((k for k in tfl), key=lambda k: kern[k + "_ms"])
-    roofline = {"bound": "mfma", "kernel": {"fwd": "fwd_kernel", "dkv": "dkv_kernel", "dq": "dq_kernel"}[dominant],
-                "achieved": round(tfl[dominant], 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(tfl[dominant] / PEAK_BF16_TFLOPS, 4), "traffic": None,
+    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dominant + "_kernel"))
+    roofline = {"bound": "mfma", "kernel": dominant + "_kernel", "achieved": round(tfl[dominant], 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl[dominant] / PEAK_BF16_TFLOPS, 4),
+                "traffic": traffic, "launch_ms": round(kern[dominant + "_ms"], 4),
+                "algorithmic_flops_per_launch": alg[dominant],
                 "per_kernel_tflops": {k: round(v, 2) for k, v in tfl.items()},
-                "per_kernel_ms_rank0": {k: round(v, 4) for k, v in kern.items()}}
+                "per_kernel_ms_mean_over_ranks": {k: round(v, 4) for k, v in kern.items()}}
 
     # ---- CPU oracle on a bounded sample of the same workload
     cpu = None
