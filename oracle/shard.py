@@ -10,6 +10,18 @@ Per-document sharding (paper Section 5.1): every document is cut into 2*CP
 chunks and worker r takes the symmetric pair r, 2*CP-1-r of every document; a
 document whose length is not divisible by 2*CP is extended with padding tokens.
 
+Padding-free per-document sharding (paper Section 5.1, "Avoid Padding"): a document of
+length L is split into a part divisible by 2*CP and the R = L mod 2*CP remaining tokens; the
+divisible part is sharded like a document of that length, the remaining tokens are dealt to
+the CP workers round-robin.  As printed, the formula defines D_i as floor(L_i / (2*CP)), a
+chunk length, while the text uses D_i as the divisible part; the reading here is
+D_i = 2*CP * floor(L_i / (2*CP)).  Also open in the paper and fixed here: the remaining tokens
+are the LAST R_i tokens of the document, and the round-robin is one counter that runs on
+across documents (token number t of all remaining tokens, in sequence order, goes to worker
+t mod CP), which is what gives every worker the same number of tokens when 2*CP divides the
+sequence length.  A rank's slots stay document-major: front chunk, back chunk, then its
+remaining tokens of that document.
+
 Readings where the paper is silent (all shared with the C library by design):
   * padding goes at the document's tail: chunk length c = ceil(L / (2*CP)),
     chunk m covers document positions [m*c, (m+1)*c), positions >= L are pads;
@@ -34,6 +46,7 @@ import numpy as np
 
 PER_DOC_PADDED = 0
 PER_SEQ = 1
+PER_DOC_NOPAD = 2
 
 
 def _segments_to_arrays(segs, doc_len):
@@ -53,7 +66,7 @@ def _segments_to_arrays(segs, doc_len):
 def shard(doc_len, cp: int, rank: int, mode: int):
     """Returns dict(q_idx, cu_seqlens_q, seg_k_begin, seg_k_end, cu_seqlens_k, useful_pairs)."""
     doc_len = [int(x) for x in doc_len]
-    if cp < 1 or not (0 <= rank < cp) or any(L <= 0 for L in doc_len) or mode not in (PER_DOC_PADDED, PER_SEQ):
+    if cp < 1 or not (0 <= rank < cp) or any(L <= 0 for L in doc_len) or mode not in (PER_DOC_PADDED, PER_SEQ, PER_DOC_NOPAD):
         raise ValueError("invalid sharding arguments")
     starts = [0]
     for L in doc_len:
@@ -70,6 +83,23 @@ def shard(doc_len, cp: int, rank: int, mode: int):
             for m in (rank, n - 1 - rank):
                 slots = [starts[d] + p if p < L else -1 for p in range(m * c, (m + 1) * c)]
                 segs.append((slots, starts[d]))
+    elif mode == PER_DOC_NOPAD:
+        t = 0                                     # running count of remaining tokens over the whole sequence
+        for d, L in enumerate(doc_len):
+            c = L // n
+            if c > 0:
+                for m in (rank, n - 1 - rank):
+                    segs.append((list(range(starts[d] + m * c, starts[d] + (m + 1) * c)), starts[d]))
+            run = []
+            for p in range(c * n, L):
+                if t % cp == rank:
+                    if run and run[-1] != starts[d] + p - 1:
+                        segs.append((run, starts[d]))
+                        run = []
+                    run.append(starts[d] + p)
+                t += 1
+            if run:
+                segs.append((run, starts[d]))
     else:
         if total % n != 0:
             raise ValueError("per-sequence sharding needs 2*CP | T")

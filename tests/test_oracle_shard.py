@@ -17,7 +17,7 @@ def _golden_cases():
             continue
         head, docs, exp = [x.strip() for x in line.split("|")]
         mode, cp, rank = head.split()
-        out.append((osh.PER_DOC_PADDED if mode == "per_doc" else osh.PER_SEQ, int(cp), int(rank),
+        out.append(({"per_doc": osh.PER_DOC_PADDED, "per_seq": osh.PER_SEQ, "per_doc_nopad": osh.PER_DOC_NOPAD}[mode], int(cp), int(rank),
                     [int(x) for x in docs.split()], [int(x) for x in exp.split()]))
     return out
 
@@ -133,3 +133,45 @@ def test_errors():
         osh.shard([4], 2, 2, osh.PER_DOC_PADDED)
     with pytest.raises(ValueError):
         osh.shard([5], 2, 0, osh.PER_SEQ)
+
+
+@pytest.mark.parametrize("cp", [2, 3, 4, 8])
+def test_padding_free_partition_and_equal_counts(cp):
+    rng = np.random.default_rng(cp)
+    docs = _rand_docs(rng, 17, 131)
+    total = sum(docs)
+    docs[-1] += (2 * cp - total % (2 * cp)) % (2 * cp)          # 2*CP | T, as the paper assumes
+    seen, sizes = [], []
+    for r in range(cp):
+        out = osh.shard(docs, cp, r, osh.PER_DOC_NOPAD)
+        q = out["q_idx"]
+        assert (q >= 0).all()                                   # no padding slots at all
+        assert (np.diff(q) > 0).all()
+        seen.extend(q.tolist())
+        sizes.append(len(q))
+    assert sorted(seen) == list(range(sum(docs)))
+    assert len(set(sizes)) == 1 and sizes[0] == sum(docs) // cp  # every worker the same number of tokens
+
+
+def test_padding_free_equals_padded_when_everything_divides():
+    docs = [16, 32, 8]
+    for r in range(4):
+        a = osh.shard(docs, 4, r, osh.PER_DOC_NOPAD)
+        b = osh.shard(docs, 4, r, osh.PER_DOC_PADDED)
+        for key in ("q_idx", "cu_seqlens_q", "seg_k_begin", "seg_k_end"):
+            assert a[key].tolist() == b[key].tolist()
+
+
+def test_padding_free_counts_differ_by_at_most_one_otherwise():
+    docs = [5, 9, 2, 31]                                         # T = 47, not divisible
+    sizes = [len(osh.shard(docs, 4, r, osh.PER_DOC_NOPAD)["q_idx"]) for r in range(4)]
+    assert max(sizes) - min(sizes) <= 1 and sum(sizes) == 47
+
+
+def test_padding_free_balances_attention_work():
+    rng = np.random.default_rng(3)
+    docs = rng.integers(200, 3000, size=12).tolist()
+    cp = 4
+    pairs = [osh.shard(docs, cp, r, osh.PER_DOC_NOPAD)["useful_pairs"] for r in range(cp)]
+    assert sum(pairs) == sum(L * (L + 1) // 2 for L in docs)
+    assert max(pairs) / (sum(pairs) / cp) < 1.02
