@@ -75,7 +75,13 @@ wlb_status wlb_pack(const int32_t* doc_len, int64_t n_docs,
  * WLB_SHARD_PER_DOC_PADDED: every document is cut into 2*cp chunks of c = ceil(L/(2*cp))
  * positions; rank r owns chunks r and 2*cp-1-r of every document; positions >= L are padding
  * and appear as slots with q_idx = -1, so every rank has the same number of slots.
- * cp == 1 is the identity map (no padding) in either mode.
+ * WLB_SHARD_PER_DOC_NOPAD (Section 5.1, "Avoid Padding"): the first 2*cp*floor(L/(2*cp)) tokens of
+ * a document are sharded as above without padding; its last L mod 2*cp tokens are dealt to the
+ * ranks round-robin by one counter that runs on across documents (remaining token number t of
+ * the sequence goes to rank t mod cp).  No slot is padding; when 2*cp | T every rank gets T/cp
+ * slots, otherwise the counts differ by at most one.  A rank's slots stay document-major: front
+ * chunk, back chunk, then its remaining tokens of that document.
+ * cp == 1 is the identity map (no padding) in every mode.
  *
  * A rank's slots are ordered document-major, front chunk before back chunk.  A segment is a
  * maximal run of slots from one chunk and one document.
@@ -94,7 +100,7 @@ wlb_status wlb_pack(const int32_t* doc_len, int64_t n_docs,
  * unknown mode, a length <= 0, per-sequence mode with T not divisible by 2*cp;
  * UNSUPPORTED when T (or the padded slot count) does not fit in int32.
  */
-enum { WLB_SHARD_PER_DOC_PADDED = 0, WLB_SHARD_PER_SEQ = 1 };
+enum { WLB_SHARD_PER_DOC_PADDED = 0, WLB_SHARD_PER_SEQ = 1, WLB_SHARD_PER_DOC_NOPAD = 2 };
 
 wlb_status wlb_shard_size(const int32_t* doc_len, int64_t n_docs, int32_t cp, int32_t rank,
                           int32_t mode, int64_t* n_q, int64_t* n_seg);

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libwlb.so")
 WLB_OK = 0
 SHARD_PER_DOC_PADDED = 0
 SHARD_PER_SEQ = 1
+SHARD_PER_DOC_NOPAD = 2
 ATTN_REUSE_PLAN = 1
 ATTN_BWD_SKIP_DELTA = 2
 ATTN_BWD_SKIP_DQ = 4

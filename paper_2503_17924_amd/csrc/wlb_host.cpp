@@ -89,7 +89,7 @@ wlb_status check_shard(const ShardArgs& a, int64_t* total_out) {
     if (!a.doc_len || a.n_docs < 1) return fail(WLB_ERR_INVALID_ARG, "wlb_shard: no documents");
     if (a.cp < 1 || a.rank < 0 || a.rank >= a.cp)
         return fail(WLB_ERR_INVALID_ARG, "wlb_shard: cp=%d rank=%d", a.cp, a.rank);
-    if (a.mode != WLB_SHARD_PER_DOC_PADDED && a.mode != WLB_SHARD_PER_SEQ)
+    if (a.mode != WLB_SHARD_PER_DOC_PADDED && a.mode != WLB_SHARD_PER_SEQ && a.mode != WLB_SHARD_PER_DOC_NOPAD)
         return fail(WLB_ERR_INVALID_ARG, "wlb_shard: unknown mode %d", a.mode);
     int64_t total = 0, padded = 0;
     const int64_t n = 2 * (int64_t)a.cp;
@@ -127,6 +127,27 @@ void walk_segments(const ShardArgs& a, int64_t total, Emit emit) {
                 const int64_t real = std::max<int64_t>(0, std::min(L, first + c) - first);
                 emit(s, first, c, real);
             }
+            s += L;
+        }
+    } else if (a.mode == WLB_SHARD_PER_DOC_NOPAD) {
+        // Section 5.1, "Avoid Padding": the part of a document divisible by 2*cp is sharded like a
+        // document of that length; its last L mod 2*cp tokens are dealt round-robin, one counter
+        // running on across documents.
+        int64_t s = 0, t = 0;
+        for (int64_t d = 0; d < a.n_docs; ++d) {
+            const int64_t L = a.doc_len[d], c = L / n;
+            if (c > 0) {
+                emit(s, a.rank * c, c, c);
+                emit(s, (n - 1 - a.rank) * c, c, c);
+            }
+            int64_t run_first = -1, run_len = 0;
+            for (int64_t p = c * n; p < L; ++p, ++t) {
+                if (t % a.cp != a.rank) continue;
+                if (run_len > 0 && run_first + run_len != p) { emit(s, run_first, run_len, run_len); run_len = 0; }
+                if (run_len == 0) run_first = p;
+                ++run_len;
+            }
+            if (run_len > 0) emit(s, run_first, run_len, run_len);
             s += L;
         }
     } else {

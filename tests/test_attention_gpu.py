@@ -198,3 +198,17 @@ def test_backward_is_deterministic():
     b = c.run_bwd()
     for x, y in zip(a, b):
         assert np.array_equal(x, y)
+
+
+def test_padding_free_sharding_forward_backward():
+    """Padding-free per-document maps go through the same kernels: the mask is per row."""
+    docs = [517, 3, 41, 1203, 66, 9, 217]          # T = 2056 = 8 * 257: every rank gets 514 slots, none padding
+    cp = 4
+    sizes = set()
+    for r in range(cp):
+        c = _small(70, docs, 8, 2, 128, cp, r, osh.PER_DOC_NOPAD)
+        assert (c.q_idx >= 0).all()
+        sizes.add(len(c.q_idx))
+        c.check_fwd(f" rank {r}")
+        c.check_bwd(f" rank {r}")
+    assert sizes == {sum(docs) // cp}

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), name
 
 
-@pytest.mark.parametrize("cp,mode", [(1, 0), (2, 0), (2, 1), (4, 0), (4, 1), (8, 0), (8, 1), (3, 0)])
+@pytest.mark.parametrize("cp,mode", [(1, 0), (2, 0), (2, 1), (4, 0), (4, 1), (8, 0), (8, 1), (3, 0), (1, 2), (2, 2), (3, 2), (4, 2), (8, 2)])
 def test_shard_matches_oracle_random(cp, mode):
     rng = np.random.default_rng(100 * cp + mode)
     for trial in range(6):
@@ -42,7 +42,7 @@ def test_shard_matches_oracle_random(cp, mode):
             assert got["useful_pairs"] == want["useful_pairs"]
 
 
-@pytest.mark.parametrize("cfg,cp,modes", [(0, 2, (0, 1)), (2, 8, (0, 1)), (4, 4, (0, 1)), (1, 1, (0,))])
+@pytest.mark.parametrize("cfg,cp,modes", [(0, 2, (0, 1, 2)), (2, 8, (0, 1, 2)), (4, 4, (0, 1, 2)), (1, 1, (0,))])
 def test_shard_matches_oracle_on_benchmark_configs(cfg, cp, modes):
     w = wl.config(cfg)
     for mode in modes:
