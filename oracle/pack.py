@@ -105,3 +105,84 @@ def imbalance(values) -> float:
     """Max over mean of a list of per-micro-batch (or per-rank) workloads."""
     values = [float(x) for x in values]
     return max(values) / (sum(values) / len(values))
+
+
+class StreamPacker:
+    """The whole of Algorithm 1 (Section 4.3) with the outlier delay of Section 4.2, as a
+    stateful object: one `step` per global batch.
+
+    `thresholds` are the queue bounds L_1 < ... < L_n.  A document of length >= L_1 is an
+    outlier and waits in queue i with L_i <= length < L_{i+1} (the last queue has no upper
+    bound).  After the current batch has been read, every queue that holds at least N
+    documents releases its N oldest ones (first in, first out) into the pending set, queues in
+    index order.  The pending set -- left-overs of the previous iteration first, then this
+    batch's ordinary documents in arrival order, then the released outliers -- is sorted by
+    length (stable) and packed greedily exactly as `pack` does; what fits nowhere is carried
+    over in that sorted order.
+
+    Readings: "greater than L_1" and "L_i <= Doc_len" disagree about length == L_1; the second
+    (inclusive) is used.  A queue holding 2N or more documents still releases N per iteration.
+    Documents longer than l_max can never be placed and are rejected.
+    """
+
+    def __init__(self, n_microbatch: int, l_max: int, a: int, b: int, thresholds=()):
+        thresholds = [int(x) for x in thresholds]
+        if n_microbatch < 1 or l_max < 1 or a < 0 or b < 0:
+            raise ValueError("invalid packer arguments")
+        if any(t <= 0 for t in thresholds) or any(x >= y for x, y in zip(thresholds, thresholds[1:])):
+            raise ValueError("thresholds must be positive and strictly increasing")
+        self.n, self.l_max, self.a, self.b = n_microbatch, l_max, a, b
+        self.thresholds = thresholds
+        self.queues = [[] for _ in thresholds]       # FIFO lists of (doc_id, length)
+        self.remained = []                           # (doc_id, length) in carried order
+        self.iteration = 0
+
+    def _queue_of(self, length):
+        q = -1
+        for i, t in enumerate(self.thresholds):
+            if length >= t:
+                q = i
+        return q
+
+    def step(self, docs):
+        """docs: iterable of (doc_id, length) in arrival order.  Returns
+        (placed, mb_len, mb_cost) where placed is a list of (doc_id, length, micro_batch) in
+        placement (sorted) order."""
+        docs = [(int(i), int(d)) for i, d in docs]
+        if any(d <= 0 or d > self.l_max for _, d in docs):
+            raise ValueError("document length out of range")
+        pending = list(self.remained)
+        for i, d in docs:
+            q = self._queue_of(d)
+            if q >= 0:
+                self.queues[q].append((i, d))
+            else:
+                pending.append((i, d))
+        for q in self.queues:
+            if len(q) >= self.n:
+                pending.extend(q[:self.n])
+                del q[:self.n]
+        order = sorted(range(len(pending)), key=lambda k: -pending[k][1])
+        work = [0] * self.n
+        length = [0] * self.n
+        placed, remained = [], []
+        for k in order:
+            i, d = pending[k]
+            w_idx = min(range(self.n), key=lambda j: (work[j], j))
+            l_idx = min(range(self.n), key=lambda j: (length[j], j))
+            if length[w_idx] + d <= self.l_max:
+                j = w_idx
+            elif length[l_idx] + d <= self.l_max:
+                j = l_idx
+            else:
+                remained.append((i, d))
+                continue
+            placed.append((i, d, j))
+            work[j] += cost(d, self.a, self.b)
+            length[j] += d
+        self.remained = remained
+        self.iteration += 1
+        return placed, length, work
+
+    def pending_counts(self):
+        return len(self.remained), sum(len(q) for q in self.queues)

@@ -126,3 +126,97 @@ def test_errors():
         opk.pack([3, 0], 2, 10, 1, 1)
     with pytest.raises(ValueError):
         opk.pack([3], 0, 10, 1, 1)
+
+
+def _stream_example():
+    path = os.path.join(os.path.dirname(__file__), "golden", "stream_packer_example.txt")
+    steps, cur = [], {}
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, rest = line.split(" ", 1)
+        if key == "batch":
+            cur = {"batch": [tuple(int(x) for x in t.split(":")) for t in rest.split()]}
+            steps.append(cur)
+        elif key == "placed":
+            cur["placed"] = [tuple(int(x) for x in t.split(":")) for t in rest.split()]
+        else:
+            cur[key] = [int(x) for x in rest.split()]
+    return steps
+
+
+def test_stream_packer_hand_worked_example():
+    sp = opk.StreamPacker(2, 20, 1, 0, thresholds=[10])
+    for st in _stream_example():
+        placed, mb_len, mb_cost = sp.step(st["batch"])
+        assert placed == st["placed"]
+        assert mb_len == st["mb_len"] and mb_cost == st["mb_cost"]
+        assert list(sp.pending_counts()) == st["state"]
+
+
+def test_stream_packer_without_queues_is_the_plain_stream():
+    rng = np.random.default_rng(9)
+    batches = [rng.integers(1, 400, size=30).tolist() for _ in range(6)]
+    want, tail = opk.pack_stream(batches, 3, 900, 2, 11)
+    sp = opk.StreamPacker(3, 900, 2, 11)
+    nid = 0
+    for cur, (docs, assign, mb_len, mb_cost) in zip(batches, want):
+        placed, got_len, got_cost = sp.step([(nid + i, d) for i, d in enumerate(cur)])
+        nid += len(cur)
+        assert got_len == mb_len and got_cost == mb_cost
+        assert sorted(d for _, d, _ in placed) == sorted(d for d, j in zip(docs, assign) if j >= 0)
+    assert sp.pending_counts() == (len(tail), 0)
+
+
+def test_stream_packer_invariants():
+    rng = np.random.default_rng(10)
+    n, l_max = 4, 3000
+    sp = opk.StreamPacker(n, l_max, 3, 100, thresholds=[800, 1600])
+    arrived, placed_ids = {}, []
+    nid = 0
+    for it in range(40):
+        batch = []
+        for _ in range(int(rng.integers(5, 25))):
+            d = int(rng.integers(1, 2500))
+            batch.append((nid, d))
+            arrived[nid] = d
+            nid += 1
+        placed, mb_len, mb_cost = sp.step(batch)
+        for i, d, j in placed:
+            assert arrived[i] == d and 0 <= j < n
+            placed_ids.append(i)
+        assert max(mb_len) <= l_max
+        lens = [d for _, d, _ in placed]
+        assert lens == sorted(lens, reverse=True)
+    assert len(placed_ids) == len(set(placed_ids))
+    rem, queued = sp.pending_counts()
+    assert len(placed_ids) + rem + queued == nid
+
+
+def test_outlier_delay_improves_balance_on_the_long_tailed_pool():
+    """Analogue of the paper's packing comparison (Section 6.4, Table 2) on the synthetic pool:
+    with L_max = 1.5 windows, queues for the very long documents lower the imbalance degree."""
+    from paper_2503_17924_amd import workloads as wl
+    w = wl.config(3)
+    window = 131072
+    seqs = opk.pack_fixed_arrival(w.doc_len, window)
+    batches = [sum(seqs[i:i + 8], []) for i in range(0, len(seqs) - 7, 8)]
+    a, b = 6, 640000
+
+    def run(thresholds):
+        sp = opk.StreamPacker(8, window * 3 // 2, a, b, thresholds=thresholds)
+        degs, nid = [], 0
+        for cur in batches:
+            placed, mb_len, mb_cost = sp.step([(nid + i, d) for i, d in enumerate(cur)])
+            nid += len(cur)
+            if min(mb_cost) > 0:
+                degs.append(opk.imbalance(mb_cost))
+        return float(np.mean(degs))
+
+    fixed = float(np.mean([opk.imbalance([sum(opk.cost(d, a, b) for d in s) for s in seqs[i:i + 8]])
+                           for i in range(0, len(seqs) - 7, 8)]))
+    plain = run([])
+    two_q = run([window // 2, window * 3 // 4])
+    assert plain < fixed
+    assert two_q < plain
