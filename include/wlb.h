@@ -68,6 +68,38 @@ wlb_status wlb_pack(const int32_t* doc_len, int64_t n_docs,
                     int32_t* assign, int64_t* mb_len, uint64_t* mb_cost);
 
 /* ------------------------------------------------------------------------------------------
+ * Streaming packer -- the whole of Algorithm 1 (Section 4.3) including the outlier delay of
+ * Section 4.2, one step per global batch.  The packer object lives in host memory and carries
+ * the algorithm's state between steps: the left-over documents and the FIFO waiting queues.
+ *
+ * thresholds[0] < ... < thresholds[n_queues-1] are the queue bounds L_1..L_n: a document of
+ * length >= L_1 is an outlier and waits in queue i with L_i <= length < L_{i+1} (the last
+ * queue is open-ended).  In a step, after the batch is read, every queue holding at least
+ * n_microbatch documents releases its n_microbatch oldest ones (queues in index order).  The
+ * pending set -- previous left-overs, then this batch's ordinary documents in arrival order,
+ * then the released outliers -- is sorted by length (stable) and packed exactly as wlb_pack
+ * does; what fits nowhere is carried over.  n_queues == 0 gives the plain streaming packer.
+ *
+ * wlb_packer_create: host; *out receives the object (free it with wlb_packer_destroy).
+ * wlb_packer_step:   host; doc_len/doc_id [n_docs] describe the arriving batch (ids are opaque
+ *   to the library).  Outputs, in placement order (longest first): out_doc_id, out_doc_len,
+ *   out_mb [capacity]; *n_out = documents placed; mb_len, mb_cost [n_microbatch].
+ *   capacity must be >= wlb_packer_pending() total + n_docs (everything that could be placed).
+ * wlb_packer_pending: host; documents carried over and documents waiting in queues.
+ * Errors: INVALID_ARG (null pointers, non-increasing thresholds, a length <= 0 or > l_max, the
+ * cost overflow rule of wlb_pack), BUFFER_TOO_SMALL (capacity).  A failed step changes nothing.
+ */
+typedef struct wlb_packer wlb_packer;
+
+wlb_status wlb_packer_create(int32_t n_microbatch, int64_t l_max, uint64_t cost_a, uint64_t cost_b,
+                             const int64_t* thresholds, int32_t n_queues, wlb_packer** out);
+void wlb_packer_destroy(wlb_packer* packer);
+wlb_status wlb_packer_step(wlb_packer* packer, const int32_t* doc_len, const int64_t* doc_id, int64_t n_docs,
+                           int64_t* out_doc_id, int32_t* out_doc_len, int32_t* out_mb, int64_t capacity,
+                           int64_t* n_out, int64_t* mb_len, uint64_t* mb_cost);
+wlb_status wlb_packer_pending(const wlb_packer* packer, int64_t* n_left_over, int64_t* n_queued);
+
+/* ------------------------------------------------------------------------------------------
  * Sharding maps (paper Section 3.1 for per-sequence, Section 5.1 for per-document).
  *
  * WLB_SHARD_PER_SEQ: the packed sequence is cut into 2*cp equal chunks; rank r owns chunks

@@ -28,7 +28,8 @@ ATTN_BWD_SKIP_DKV = 8
 STATUS_NAMES = {0: "WLB_OK", 1: "WLB_ERR_INVALID_ARG", 2: "WLB_ERR_BUFFER_TOO_SMALL",
                 3: "WLB_ERR_UNSUPPORTED", 4: "WLB_ERR_HIP"}
 
-EXPORTS = ["wlb_last_error", "wlb_pack", "wlb_shard_size", "wlb_shard", "wlb_attn_workspace_size",
+EXPORTS = ["wlb_last_error", "wlb_pack", "wlb_packer_create", "wlb_packer_destroy", "wlb_packer_step",
+           "wlb_packer_pending", "wlb_shard_size", "wlb_shard", "wlb_attn_workspace_size",
            "wlb_attn_plan", "wlb_attn_plan_layout", "wlb_attn_fwd", "wlb_attn_bwd"]
 
 
@@ -67,6 +68,8 @@ def lib():
         L.wlb_last_error.restype = C.c_char_p
         for name in EXPORTS[1:]:
             getattr(L, name).restype = C.c_int
+        L.wlb_packer_destroy.restype = None
+        L.wlb_packer_destroy.argtypes = [C.c_void_p]
         _lib = L
     return _lib
 
@@ -96,6 +99,52 @@ def wlb_pack(doc_len, n_microbatch: int, l_max: int, cost_a: int, cost_b: int):
                           C.c_uint64(cost_a), C.c_uint64(cost_b), _np_ptr(assign, C.c_int32),
                           _np_ptr(mb_len, C.c_int64), _np_ptr(mb_cost, C.c_uint64)))
     return assign, mb_len[:n_microbatch], mb_cost[:n_microbatch]
+
+
+class Packer:
+    """wlb_packer_create / wlb_packer_step / wlb_packer_pending / wlb_packer_destroy."""
+
+    def __init__(self, n_microbatch: int, l_max: int, cost_a: int, cost_b: int, thresholds=()):
+        th = np.ascontiguousarray(list(thresholds), dtype=np.int64)
+        self.n = n_microbatch
+        self._h = C.c_void_p(0)
+        _check(lib().wlb_packer_create(C.c_int32(n_microbatch), C.c_int64(l_max), C.c_uint64(cost_a),
+                                       C.c_uint64(cost_b), _np_ptr(th, C.c_int64) if len(th) else None,
+                                       C.c_int32(len(th)), C.byref(self._h)))
+
+    def pending(self):
+        a, b = C.c_int64(0), C.c_int64(0)
+        _check(lib().wlb_packer_pending(self._h, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    def step(self, doc_id, doc_len):
+        """-> (placed doc ids, their lengths, their micro-batch, mb_len, mb_cost)"""
+        doc_len = _i32(doc_len)
+        doc_id = np.ascontiguousarray(doc_id, dtype=np.int64)
+        cap = sum(self.pending()) + len(doc_len)
+        oid = np.empty(max(cap, 1), dtype=np.int64)
+        olen = np.empty(max(cap, 1), dtype=np.int32)
+        omb = np.empty(max(cap, 1), dtype=np.int32)
+        mb_len = np.empty(self.n, dtype=np.int64)
+        mb_cost = np.empty(self.n, dtype=np.uint64)
+        n_out = C.c_int64(0)
+        _check(lib().wlb_packer_step(self._h, _np_ptr(doc_len, C.c_int32), _np_ptr(doc_id, C.c_int64),
+                                     C.c_int64(len(doc_len)), _np_ptr(oid, C.c_int64), _np_ptr(olen, C.c_int32),
+                                     _np_ptr(omb, C.c_int32), C.c_int64(cap), C.byref(n_out),
+                                     _np_ptr(mb_len, C.c_int64), _np_ptr(mb_cost, C.c_uint64)))
+        k = n_out.value
+        return oid[:k], olen[:k], omb[:k], mb_len, mb_cost
+
+    def close(self):
+        if self._h:
+            lib().wlb_packer_destroy(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def wlb_shard_size(doc_len, cp: int, rank: int, mode: int):

@@ -77,6 +77,113 @@ extern "C" wlb_status wlb_pack(const int32_t* doc_len, int64_t n_docs, int32_t n
 }
 
 // ---------------------------------------------------------------------------------------
+// Streaming packer: Algorithm 1 with the outlier waiting queues of Section 4.2.
+// ---------------------------------------------------------------------------------------
+struct wlb_packer {
+    struct Doc { int64_t id; int32_t len; };
+    int32_t n;
+    int64_t l_max;
+    uint64_t a, b;
+    std::vector<int64_t> thresholds;
+    std::vector<std::vector<Doc>> queues;   // FIFO: front = oldest
+    std::vector<Doc> left_over;
+};
+
+static bool cost_fits(uint64_t cost_a, uint64_t cost_b, int64_t l_max) {
+    unsigned __int128 lm = (unsigned __int128)(uint64_t)l_max;
+    if (cost_a != 0 && (lm * lm) > (~(unsigned __int128)0) / cost_a) return false;
+    unsigned __int128 worst = (unsigned __int128)cost_a * lm * lm + (unsigned __int128)cost_b * lm;
+    return worst <= (unsigned __int128)std::numeric_limits<uint64_t>::max();
+}
+
+extern "C" wlb_status wlb_packer_create(int32_t n_microbatch, int64_t l_max, uint64_t cost_a, uint64_t cost_b,
+                                        const int64_t* thresholds, int32_t n_queues, wlb_packer** out) {
+    if (!out) return fail(WLB_ERR_INVALID_ARG, "wlb_packer_create: null output");
+    *out = nullptr;
+    if (n_microbatch < 1 || l_max < 1 || n_queues < 0 || (n_queues > 0 && !thresholds))
+        return fail(WLB_ERR_INVALID_ARG, "wlb_packer_create: n_microbatch=%d l_max=%lld n_queues=%d", n_microbatch,
+                    (long long)l_max, n_queues);
+    if (!cost_fits(cost_a, cost_b, l_max))
+        return fail(WLB_ERR_INVALID_ARG, "wlb_packer_create: cost_a*l_max^2 + cost_b*l_max overflows 64 bits");
+    for (int i = 0; i < n_queues; ++i)
+        if (thresholds[i] <= 0 || (i > 0 && thresholds[i] <= thresholds[i - 1]))
+            return fail(WLB_ERR_INVALID_ARG, "wlb_packer_create: thresholds must be positive and strictly increasing");
+    wlb_packer* p = new wlb_packer;
+    p->n = n_microbatch; p->l_max = l_max; p->a = cost_a; p->b = cost_b;
+    p->thresholds.assign(thresholds, thresholds + n_queues);
+    p->queues.resize((size_t)n_queues);
+    *out = p;
+    return WLB_OK;
+}
+
+extern "C" void wlb_packer_destroy(wlb_packer* packer) { delete packer; }
+
+extern "C" wlb_status wlb_packer_pending(const wlb_packer* packer, int64_t* n_left_over, int64_t* n_queued) {
+    if (!packer || !n_left_over || !n_queued) return fail(WLB_ERR_INVALID_ARG, "wlb_packer_pending: null pointer");
+    *n_left_over = (int64_t)packer->left_over.size();
+    int64_t q = 0;
+    for (const auto& v : packer->queues) q += (int64_t)v.size();
+    *n_queued = q;
+    return WLB_OK;
+}
+
+extern "C" wlb_status wlb_packer_step(wlb_packer* packer, const int32_t* doc_len, const int64_t* doc_id, int64_t n_docs,
+                                      int64_t* out_doc_id, int32_t* out_doc_len, int32_t* out_mb, int64_t capacity,
+                                      int64_t* n_out, int64_t* mb_len, uint64_t* mb_cost) {
+    if (!packer || !n_out || !mb_len || !mb_cost || n_docs < 0 || (n_docs > 0 && (!doc_len || !doc_id)))
+        return fail(WLB_ERR_INVALID_ARG, "wlb_packer_step: null pointer or negative count");
+    for (int64_t i = 0; i < n_docs; ++i)
+        if (doc_len[i] <= 0 || doc_len[i] > packer->l_max)
+            return fail(WLB_ERR_INVALID_ARG, "wlb_packer_step: doc_len[%lld]=%d outside (0, l_max]", (long long)i, doc_len[i]);
+    int64_t queued = 0;
+    for (const auto& v : packer->queues) queued += (int64_t)v.size();
+    const int64_t could_place = (int64_t)packer->left_over.size() + queued + n_docs;
+    if (capacity < could_place || (could_place > 0 && (!out_doc_id || !out_doc_len || !out_mb)))
+        return fail(WLB_ERR_BUFFER_TOO_SMALL, "wlb_packer_step: capacity %lld < %lld", (long long)capacity, (long long)could_place);
+
+    using Doc = wlb_packer::Doc;
+    std::vector<Doc> pending(packer->left_over);
+    for (int64_t i = 0; i < n_docs; ++i) {
+        int q = -1;
+        for (size_t t = 0; t < packer->thresholds.size(); ++t)
+            if (doc_len[i] >= packer->thresholds[t]) q = (int)t;
+        if (q >= 0) packer->queues[(size_t)q].push_back(Doc{doc_id[i], doc_len[i]});
+        else pending.push_back(Doc{doc_id[i], doc_len[i]});
+    }
+    for (auto& q : packer->queues)
+        if ((int64_t)q.size() >= packer->n) {
+            pending.insert(pending.end(), q.begin(), q.begin() + packer->n);
+            q.erase(q.begin(), q.begin() + packer->n);
+        }
+    std::stable_sort(pending.begin(), pending.end(), [](const Doc& x, const Doc& y) { return x.len > y.len; });
+
+    const int n = packer->n;
+    for (int j = 0; j < n; ++j) { mb_len[j] = 0; mb_cost[j] = 0; }
+    packer->left_over.clear();
+    int64_t placed = 0;
+    for (const Doc& doc : pending) {
+        const uint64_t d = (uint64_t)doc.len;
+        int w = 0, l = 0;
+        for (int j = 1; j < n; ++j) {
+            if (mb_cost[j] < mb_cost[w]) w = j;
+            if (mb_len[j] < mb_len[l]) l = j;
+        }
+        int dst;
+        if (mb_len[w] + (int64_t)d <= packer->l_max) dst = w;
+        else if (mb_len[l] + (int64_t)d <= packer->l_max) dst = l;
+        else { packer->left_over.push_back(doc); continue; }
+        out_doc_id[placed] = doc.id;
+        out_doc_len[placed] = doc.len;
+        out_mb[placed] = dst;
+        ++placed;
+        mb_len[dst] += (int64_t)d;
+        mb_cost[dst] += packer->a * d * d + packer->b * d;
+    }
+    *n_out = placed;
+    return WLB_OK;
+}
+
+// ---------------------------------------------------------------------------------------
 // Sharding maps (Section 3.1 per-sequence; Section 5.1 per-document with tail padding).
 // ---------------------------------------------------------------------------------------
 namespace {

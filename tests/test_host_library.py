@@ -131,3 +131,46 @@ def test_attention_argument_checks_need_no_gpu():
     # null pointers are rejected before anything is launched
     st = B.lib().wlb_attn_fwd(ctypes.byref(d), None, None, None, None, None, None, None, None, ctypes.c_size_t(0), None)
     assert st == 1 and b"null" in B.lib().wlb_last_error()
+
+
+@pytest.mark.parametrize("thresholds,l_max", [((), 131072), ((65536,), 196608), ((65536, 98304), 196608),
+                                              ((32768, 65536, 98304), 131072)])
+def test_stream_packer_matches_oracle_on_the_document_pool(thresholds, l_max):
+    w = wl.config(3)
+    seqs = opk.pack_fixed_arrival(w.doc_len, 131072)
+    batches = [sum(seqs[i:i + 8], []) for i in range(0, len(seqs) - 7, 8)]
+    ref = opk.StreamPacker(8, l_max, 6, 640000, thresholds=thresholds)
+    got = B.Packer(8, l_max, 6, 640000, thresholds)
+    nid = 0
+    for cur in batches:
+        ids = list(range(nid, nid + len(cur)))
+        nid += len(cur)
+        placed, mb_len, mb_cost = ref.step(zip(ids, cur))
+        oid, olen, omb, glen, gcost = got.step(ids, cur)
+        assert list(zip(oid.tolist(), olen.tolist(), omb.tolist())) == placed
+        assert glen.tolist() == mb_len and gcost.tolist() == mb_cost
+        assert got.pending() == ref.pending_counts()
+    got.close()
+
+
+def test_stream_packer_random_and_errors():
+    rng = np.random.default_rng(77)
+    ref = opk.StreamPacker(3, 500, 1, 7, thresholds=[200, 350])
+    got = B.Packer(3, 500, 1, 7, [200, 350])
+    nid = 0
+    for it in range(60):
+        cur = rng.integers(1, 500, size=int(rng.integers(0, 12))).tolist()
+        ids = list(range(nid, nid + len(cur)))
+        nid += len(cur)
+        placed, mb_len, mb_cost = ref.step(zip(ids, cur))
+        oid, olen, omb, glen, gcost = got.step(ids, cur)
+        assert list(zip(oid.tolist(), olen.tolist(), omb.tolist())) == placed
+        assert glen.tolist() == mb_len and gcost.tolist() == mb_cost
+    before = got.pending()
+    with pytest.raises(B.WlbError):
+        got.step([nid], [501])                      # longer than l_max: rejected, state unchanged
+    assert got.pending() == before
+    with pytest.raises(B.WlbError):
+        B.Packer(3, 500, 1, 7, [300, 300])
+    with pytest.raises(B.WlbError):
+        B.Packer(0, 500, 1, 7)
