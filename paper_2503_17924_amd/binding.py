@@ -14,7 +14,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libwlb.so")
+# WLB_LIBRARY selects another build of the library (e.g. one made with different compiler flags)
+LIB_PATH = os.environ.get("WLB_LIBRARY") or os.path.join(_HERE, "libwlb.so")
 
 WLB_OK = 0
 SHARD_PER_DOC_PADDED = 0

@@ -24,15 +24,19 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False, keep_asm: bool = False) -> str:
+def build(verbose: bool = False, keep_asm: bool = False, lib_out: str | None = None) -> str:
+    """Compiles every source and links the library (to `lib_out`, default in-tree libwlb.so).
+    WLB_HIPCC_EXTRA adds compiler flags (space separated) to every compile line."""
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
-    bdir = os.path.join(ROOT, "_build")
+    extra = os.environ.get("WLB_HIPCC_EXTRA", "").split()
+    lib_out = lib_out or LIB
+    bdir = os.path.join(ROOT, "_build" if lib_out == LIB else "_build/" + os.path.basename(lib_out))
     os.makedirs(bdir, exist_ok=True)
     objs = []
     procs = []
     for src in SOURCES:
         obj = os.path.join(bdir, os.path.splitext(src)[0] + ".o")
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         if src.endswith(".cpp"):
             cmd[1:1] = ["-x", "hip"]
         if "attn" in src:
@@ -53,14 +57,15 @@ def build(verbose: bool = False, keep_asm: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
         if verbose and out.strip():
             print(out)
-    tmp = LIB + ".tmp"
+    tmp = lib_out + ".tmp"
     link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp]
     r = subprocess.run(link, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib_out)
+    return lib_out
 
 
 if __name__ == "__main__":
-    print(build(verbose=True, keep_asm="--asm" in sys.argv))
+    _out = [a.split("=", 1)[1] for a in sys.argv if a.startswith("--out=")]
+    print(build(verbose=True, keep_asm="--asm" in sys.argv, lib_out=os.path.abspath(_out[0]) if _out else None))

@@ -88,7 +88,7 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
     const int tile = p.fwd_order[rank];
     const int h = hk * G + hh;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int j16 = lane & 15, gi = (lane >> 4) & 1;
 
@@ -114,7 +114,8 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
     vrs.init(p.v + (size_t)hk * D, kv_bytes);
     TileDma<D, BN, NW> dma;
     dma.init(wave, lane, kv_row);
-    auto tile_ptr = [&](int which) { return reinterpret_cast<__bf16*>(smem + which * TILEB); };
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
+    auto tile_ptr = [&](int which) { return smem_base + (uint32_t)(which * TILEB); };
     if (jb < je) {
         dma.issue(krs, tile_ptr(0), jb * BN, wave);
         dma.issue(vrs, tile_ptr(2), jb * BN, wave);
@@ -146,7 +147,6 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
     }
 
     int naddr[KS], taddr[DB][2];
-    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) naddr[ks] = smem_base + l32 * ROWB + swz<CPR>(l32, ks * 2 + half) * 16;
 #pragma unroll
@@ -274,8 +274,10 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
     const int kt = p.key_order[rank];
     const int k0 = kt * BNK;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int role = wave >> 2, kblk = wave & 3;
+    const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
+    // role and key block are left as per-lane values: as scalars they raise the register pressure
+    // of the two role branches past 256 (spills)
+    const int role = tid >> 8, kblk = (tid >> 6) & 3;
     const int l32 = lane & 31, half = lane >> 5;
     const int j16 = lane & 15, gi = (lane >> 4) & 1;
     const int kw0 = k0 + kblk * 32;
@@ -310,7 +312,8 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
     const uint32_t q_total = (uint32_t)p.n_q * q_row * 2u;
     TileDma<D, GR, NW> dma;
     dma.init(wave, lane, q_row);
-    auto tile_ptr = [&](int which) { return reinterpret_cast<__bf16*>(smem + which * TILEB); };
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
+    auto tile_ptr = [&](int which) { return smem_base + (uint32_t)(which * TILEB); };
     auto issue_stage = [&](int g, int h, int buf) {
         BufRsrc qrs, ors;
         qrs.init(p.q + (size_t)h * D, q_total - (uint32_t)h * ROWB);
@@ -318,18 +321,30 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
         dma.issue(qrs, tile_ptr(buf), g * GR, wave);
         dma.issue(ors, tile_ptr(2 + buf), g * GR, wave);
     };
-    float r_lse = INFINITY, r_dl = 0.f;
-    int r_lo = kPadLo, r_hi = 0;
-    auto load_small = [&](int g, int h) {
-        if (tid < GR) {
-            const int rowi = g * GR + tid;
-            const bool inr = rowi < p.n_q;
-            const int rc = inr ? rowi : p.n_q - 1;
-            r_hi = inr ? p.row_hi[rc] : 0;
-            const bool real = r_hi > 0;
-            r_lo = real ? p.row_lo[rc] : kPadLo;
-            r_lse = inr ? p.lse2[(size_t)h * p.n_q + rc] : INFINITY;     // already +inf / 0 for padding rows
-            r_dl = inr ? p.delta[(size_t)h * p.n_q + rc] : 0.f;
+    // Per-row scalars of a stage (visible key interval, log2-scaled LSE, delta) are copied
+    // global->LDS asynchronously as well, by wavefront 0: no register load sits between the copies
+    // and the compute, so nothing makes the compiler wait on vector memory while they are in
+    // flight.  Rows past n_q read as zeros (row_hi = 0: no visible key; their Q/dO rows are zero).
+    BufRsrc lo_rs, hi_rs;
+    lo_rs.init(p.row_lo, (uint32_t)p.n_q * 4u);
+    hi_rs.init(p.row_hi, (uint32_t)p.n_q * 4u);
+    lo_rs.make_uniform();
+    hi_rs.make_uniform();
+    auto load_small = [&](int g, int h, int b) {
+        if (wave == 0) {
+            BufRsrc ls_rs, dl_rs;
+            ls_rs.init(p.lse2 + (size_t)h * p.n_q, (uint32_t)p.n_q * 4u);
+            dl_rs.init(p.delta + (size_t)h * p.n_q, (uint32_t)p.n_q * 4u);
+            ls_rs.make_uniform();
+            dl_rs.make_uniform();
+            const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)(g * GR) * 4u);
+            auto lds_of = [&](const void* ptr) __attribute__((always_inline)) {
+                return (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)(WLB_LDS const void*)ptr);
+            };
+            dma_issue_256(lo_rs.r, lds_of(&lo_s[b][0]), lane * 4, soff);
+            dma_issue_256(hi_rs.r, lds_of(&hi_s[b][0]), lane * 4, soff);
+            dma_issue_256(ls_rs.r, lds_of(&lse_s[b][0]), lane * 4, soff);
+            dma_issue_256(dl_rs.r, lds_of(&dl_s[b][0]), lane * 4, soff);
         }
     };
 
@@ -344,14 +359,13 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
             const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
             taddr[db][t] = qq * ROWB + swz<CPR>(qq, dch) * 16 + (j16 & 1) * 8;
         }
-    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
     const uint32_t pbuf_lane = (uint32_t)(uintptr_t)(WLB_LDS char*)pbuf + kblk * 4096 + lane * 16;
 
     int g = next_group(p.key_range[2 * kt]);
     int hh = 0, buf = 0;
     if (g < g_end) {
         issue_stage(g, hk * G, 0);
-        load_small(g, hk * G);
+        load_small(g, hk * G, 0);
     }
     while (g < g_end) {
         int gn = g, hn = hh + 1;
@@ -361,12 +375,11 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
         const bool wave_live = (gd.x < kw0 + 32) && (gd.y > kw0);
         const bool has_pads = p.group_real[g] < min(GR, p.n_q - g * GR);
 
-        if (tid < GR) { lse_s[buf][tid] = r_lse; dl_s[buf][tid] = r_dl; lo_s[buf][tid] = r_lo; hi_s[buf][tid] = r_hi; }
         wait_vmem();
         __syncthreads();      // barrier 1: stage (g, hh) is in LDS; everyone has left the other buffers and pbuf
         if (gn < g_end) {
             issue_stage(gn, hk * G + hn, buf ^ 1);
-            load_small(gn, hk * G + hn);
+            load_small(gn, hk * G + hn, buf ^ 1);
         }
         if (has_pads) {
             const int r = tid >> 3, part = tid & 7;       // 512 threads: 8 per row
@@ -387,24 +400,27 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
         f32x16 dp[2];             // gradient role: dP
         if (wave_live) {
             if (role == 0) {
-                // all 16 Q operands are requested before the first MFMA, the two row blocks'
-                // accumulation chains are interleaved
-                bf16x8 qa[2][KS];
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                    for (int qb = 0; qb < 2; ++qb)
-                        qa[qb][ks] = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(qb_base + naddr[ks] + qb * 32 * ROWB));
+                // operands are requested half the head dimension at a time (8 reads in flight),
+                // the two row blocks' accumulation chains are interleaved
                 f32x16 s2[2];
 #pragma unroll
                 for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) s2[qb][r] = 0.f;
-                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
+                for (int kh = 0; kh < 2; ++kh) {
+                    bf16x8 qa[2][KS / 2];
 #pragma unroll
-                    for (int qb = 0; qb < 2; ++qb) s2[qb] = mfma32(qa[qb][ks], bop[ks], s2[qb]);
+                    for (int ks = 0; ks < KS / 2; ++ks)
+#pragma unroll
+                        for (int qb = 0; qb < 2; ++qb)
+                            qa[qb][ks] = *reinterpret_cast<const WLB_LDS bf16x8*>(
+                                (uintptr_t)(qb_base + naddr[kh * (KS / 2) + ks] + qb * 32 * ROWB));
+#pragma unroll
+                    for (int ks = 0; ks < KS / 2; ++ks)
+#pragma unroll
+                        for (int qb = 0; qb < 2; ++qb) s2[qb] = mfma32(qa[qb][ks], bop[kh * (KS / 2) + ks], s2[qb]);
+                }
 #pragma unroll
                 for (int qb = 0; qb < 2; ++qb) {
                     const f32x16 s = s2[qb];
@@ -432,21 +448,24 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
                     }
                 }
             } else {
-                bf16x8 ga[2][KS];
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                    for (int qb = 0; qb < 2; ++qb)
-                        ga[qb][ks] = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(ob_base + naddr[ks] + qb * 32 * ROWB));
 #pragma unroll
                 for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) dp[qb][r] = 0.f;
-                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
+                for (int kh = 0; kh < 2; ++kh) {
+                    bf16x8 ga[2][KS / 2];
 #pragma unroll
-                    for (int qb = 0; qb < 2; ++qb) dp[qb] = mfma32(ga[qb][ks], bop[ks], dp[qb]);
+                    for (int ks = 0; ks < KS / 2; ++ks)
+#pragma unroll
+                        for (int qb = 0; qb < 2; ++qb)
+                            ga[qb][ks] = *reinterpret_cast<const WLB_LDS bf16x8*>(
+                                (uintptr_t)(ob_base + naddr[kh * (KS / 2) + ks] + qb * 32 * ROWB));
+#pragma unroll
+                    for (int ks = 0; ks < KS / 2; ++ks)
+#pragma unroll
+                        for (int qb = 0; qb < 2; ++qb) dp[qb] = mfma32(ga[qb][ks], bop[kh * (KS / 2) + ks], dp[qb]);
+                }
             }
         }
         __syncthreads();      // barrier 2: P of this stage is visible to the partners

@@ -53,7 +53,7 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
     const int tile = p.order[rank];
     const int h = hk * G + hh;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int j16 = lane & 15, gi = (lane >> 4) & 1;
 
@@ -81,7 +81,8 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
     dma.init(wave, lane, kv_row);
     TileDma<D, 32, NW> dma_half;
     dma_half.init(wave, lane, kv_row);
-    auto tile_ptr = [&](int which) { return reinterpret_cast<__bf16*>(smem + which * TILEB); };
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
+    auto tile_ptr = [&](int which) { return smem_base + (uint32_t)(which * TILEB); };
     if (jb < je) {
         dma_half.issue(krs, tile_ptr(1), jb * BN, wave);            // keys [64jb, 64jb+32) for the first scores
         dma.issue(krs, tile_ptr(0), jb * BN + 32, wave);            // shifted K tile jb
@@ -122,7 +123,6 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
 
     // ---- LDS addresses: per-lane registers that already contain the tile base, so that inside
     // the (two-fold unrolled) tile loop every access is register + immediate
-    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) kaddr[ks] += smem_base;
 #pragma unroll
@@ -236,6 +236,10 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
         wait_vmem();
         __syncthreads();
     };
+    // The compiler's wait-count bookkeeping does not see the asynchronous copies.  Draining the
+    // vector-memory counter here, on every path into the loop, keeps it from placing counted waits
+    // for the Q operand loads inside the loop, where they would wait for the copies in flight.
+    wait_vmem();
     for (int j = jb; j < je; j += 2) {
         tile_step(j, std::integral_constant<int, 0>{});
         if (j + 1 < je) tile_step(j + 1, std::integral_constant<int, 1>{});

@@ -66,6 +66,10 @@ __device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3) 
     return r;
 }
 
+// tells the compiler that a value is the same in every lane (moves it to a scalar register)
+__device__ __forceinline__ uint32_t uniform(uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); }
+__device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
 // XOR swizzle of the 16-byte chunks of an unpadded row-major LDS tile whose rows hold CPR
 // chunks: logical chunk cc of row r is stored at chunk swz(r, cc).  With 256-byte rows it
 // makes both access patterns of the kernels bank-conflict free: 16 rows x one chunk (b128
@@ -129,15 +133,15 @@ struct TileDma {
             voff[n] = ri * (int)row_bytes + cc * 16;
         }
     }
-    // rows row0 .. row0+ROWS-1 of the tensor -> lds_tile (ROWS * D * 2 bytes)
-    __device__ __forceinline__ void issue(const BufRsrc& rs, __bf16* lds_tile, int row0, int wave) const {
+    // rows row0 .. row0+ROWS-1 of the tensor -> the tile at LDS byte address lds_tile (ROWS * D * 2
+    // bytes).  `wave` must be wave-uniform in the compiler's eyes (take it through uniform()), so
+    // that the LDS address and the row offset are computed on the scalar unit.
+    __device__ __forceinline__ void issue(const BufRsrc& rs, uint32_t lds_tile, int row0, int wave) const {
 #pragma unroll
         for (int n = 0; n < PER; ++n) {
             const int blk = wave * PER + n;
             const uint32_t soff = (uint32_t)(row0 + blk * RPI) * row_bytes;
-            const uint32_t lds_addr = (uint32_t)(uintptr_t)(WLB_LDS void*)(lds_tile + blk * 512);
-            dma_issue_1k(rs.r, __builtin_amdgcn_readfirstlane(lds_addr), voff[n],
-                         __builtin_amdgcn_readfirstlane(soff));
+            dma_issue_1k(rs.r, uniform(lds_tile + (uint32_t)blk * 1024u), voff[n], uniform(soff));
         }
     }
 };
