@@ -199,8 +199,13 @@ def main():
     tfl = {k: alg[k] / (kern[k + "_ms"] * 1e-3) / 1e12 for k in alg if k + "_ms" in kern}
     dominant = max((k for k in tfl), key=lambda k: kern[k + "_ms"])
     traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dominant + "_kernel"))
+    # the dense bf16 MFMA rate this GPU sustains (a kernel of nothing but MFMAs on register operands):
+    # lower for random operand values -- what attention sees -- than for all-ones
+    ceiling = {"all_ones": round(B.mfma_ceiling(False), 1), "random": round(B.mfma_ceiling(True), 1)}
     roofline = {"bound": "mfma", "kernel": dominant + "_kernel", "achieved": round(tfl[dominant], 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl[dominant] / PEAK_BF16_TFLOPS, 4),
+                "measured_mfma_ceiling_tflops": ceiling,
+                "frac_of_measured_ceiling_random_operands": round(tfl[dominant] / ceiling["random"], 4),
                 "traffic": traffic, "launch_ms": round(kern[dominant + "_ms"], 4),
                 "algorithmic_flops_per_launch": alg[dominant],
                 "per_kernel_tflops": {k: round(v, 2) for k, v in tfl.items()},
@@ -243,6 +248,7 @@ def main():
                    "head_dim": D, "n_docs": int(len(w.doc_len)), "longest_doc": int(w.doc_len.max()),
                    "sharding": "per_document_padded", "useful_pairs": int(pairs)},
         "pct_of_bf16_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "pct_of_measured_mfma_ceiling_random_operands": round(100.0 * value / ceiling["random"], 2),
         "per_rank_latency": per_rank,
         "host_us_per_step": {k: round(v / args.steps, 1) for k, v in host_us.items()},
         "roofline": roofline, "cpu_baseline": cpu, "setup_s": round(setup_s, 1),

@@ -229,6 +229,18 @@ wlb_status wlb_attn_bwd(const wlb_attn_desc* desc, const void* q, const void* k,
                         void* dq, void* dk, void* dv,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Measurement aid (not part of the method): one launch of a kernel that issues only dense
+ * 32x32x16 bf16 MFMAs on register operands, to measure the MFMA rate the GPU sustains.  The
+ * attention kernels are MFMA bound on long documents (Section 5.2 quotes kernel efficiency as
+ * achieved TFLOPs); on MI355X the sustained rate depends on the operand values, so
+ * random_operands selects all-ones (0) or pseudo-random values in [-1, 1) (1).
+ * sink: device, >= 4 bytes, never written in practice.  *flops (host) receives the floating-point
+ * operations the launch performs; the caller times the launch on `stream`.  Asynchronous.
+ * Errors: INVALID_ARG (null pointer, n_iter outside [1, 2^20]), HIP (launch failure).
+ */
+wlb_status wlb_calib_mfma(int32_t random_operands, int32_t n_iter, float* sink, double* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

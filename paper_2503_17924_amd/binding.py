@@ -30,7 +30,7 @@ STATUS_NAMES = {0: "WLB_OK", 1: "WLB_ERR_INVALID_ARG", 2: "WLB_ERR_BUFFER_TOO_SM
                 3: "WLB_ERR_UNSUPPORTED", 4: "WLB_ERR_HIP"}
 
 EXPORTS = ["wlb_last_error", "wlb_pack", "wlb_packer_create", "wlb_packer_destroy", "wlb_packer_step",
-           "wlb_packer_pending", "wlb_shard_size", "wlb_shard", "wlb_attn_workspace_size",
+           "wlb_packer_pending", "wlb_calib_mfma", "wlb_shard_size", "wlb_shard", "wlb_attn_workspace_size",
            "wlb_attn_plan", "wlb_attn_plan_layout", "wlb_attn_fwd", "wlb_attn_bwd"]
 
 
@@ -100,6 +100,27 @@ def wlb_pack(doc_len, n_microbatch: int, l_max: int, cost_a: int, cost_b: int):
                           C.c_uint64(cost_a), C.c_uint64(cost_b), _np_ptr(assign, C.c_int32),
                           _np_ptr(mb_len, C.c_int64), _np_ptr(mb_cost, C.c_uint64)))
     return assign, mb_len[:n_microbatch], mb_cost[:n_microbatch]
+
+
+def mfma_ceiling(random_operands: bool, n_iter: int = 4000, reps: int = 8) -> float:
+    """Sustained dense bf16 MFMA TFLOP/s of the current GPU, measured with wlb_calib_mfma."""
+    import torch
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    flops = C.c_double(0.0)
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def launch():
+        _check(lib().wlb_calib_mfma(C.c_int32(int(random_operands)), C.c_int32(n_iter), C.c_void_p(sink.data_ptr()),
+                                    C.byref(flops), stream))
+    for _ in range(reps):       # clocks settle over the first few milliseconds
+        launch()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        launch()
+    e1.record()
+    torch.cuda.synchronize()
+    return flops.value * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
 
 class Packer:

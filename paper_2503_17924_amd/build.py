@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwlb.so")
-SOURCES = ["wlb_host.cpp", "wlb_plan.hip", "wlb_attn_fwd.hip", "wlb_attn_bwd.hip"]
+SOURCES = ["wlb_host.cpp", "wlb_plan.hip", "wlb_attn_fwd.hip", "wlb_attn_bwd.hip", "wlb_calib.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
