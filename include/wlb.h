@@ -230,6 +230,37 @@ wlb_status wlb_attn_bwd(const wlb_attn_desc* desc, const void* q, const void* k,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Adaptive sharding selection (Section 5.3): predict the attention forward+backward latency of a
+ * micro-batch under per-sequence and under per-document sharding and pick the faster one.
+ * Per segment of the sharding map (a rank's run of slots inside one chunk of one document; shape
+ * Q_len = slots, KV_len = keys its last row sees): operations = padded pairs * 14 * head_dim * hq,
+ * where the rows are cut into tiles of tile_q rows and a tile ending at local row e counts
+ * tile_q * roundup(KV_len - Q_len + e, tile_k) pairs; rate = bilinear interpolation of the profiled
+ * TFLOP/s table in (Q_len, KV_len), clamped at the grid edges; latency = operations / rate.  A
+ * rank's latency is the sum over its segments, a sharding's latency the maximum over ranks.
+ * The table comes from profiling this library's kernels offline; all pointers are host memory.
+ *
+ * wlb_predict_latency: rank_latency [cp] (seconds) for `mode` (a WLB_SHARD_* value).
+ * wlb_select_sharding: *mode = WLB_SHARD_PER_DOC_PADDED if its latency is strictly lower, else
+ *   WLB_SHARD_PER_SEQ; the two predicted latencies are returned as well.
+ * Errors: INVALID_ARG (null pointers, grids not strictly increasing, non-positive rates, and
+ * every error of wlb_shard for the same documents / cp / mode).
+ */
+typedef struct {
+    int32_t n_q, n_kv;          /* grid sizes */
+    const int32_t* q_len;       /* [n_q]  strictly increasing */
+    const int32_t* kv_len;      /* [n_kv] strictly increasing */
+    const double* tflops;       /* [n_q][n_kv] achieved TFLOP/s (executed operations / time) */
+    int32_t tile_q, tile_k;     /* the kernel's tile: rows per query tile, keys per key tile */
+} wlb_kernel_profile;
+
+wlb_status wlb_predict_latency(const int32_t* doc_len, int64_t n_docs, int32_t cp, int32_t mode, int32_t hq,
+                               int32_t head_dim, const wlb_kernel_profile* profile, double* rank_latency);
+wlb_status wlb_select_sharding(const int32_t* doc_len, int64_t n_docs, int32_t cp, int32_t hq, int32_t head_dim,
+                               const wlb_kernel_profile* profile, int32_t* mode, double* latency_per_seq,
+                               double* latency_per_doc);
+
+/* ------------------------------------------------------------------------------------------
  * Measurement aid (not part of the method): one launch of a kernel that issues only dense
  * 32x32x16 bf16 MFMAs on register operands, to measure the MFMA rate the GPU sustains.  The
  * attention kernels are MFMA bound on long documents (Section 5.2 quotes kernel efficiency as

@@ -30,7 +30,7 @@ STATUS_NAMES = {0: "WLB_OK", 1: "WLB_ERR_INVALID_ARG", 2: "WLB_ERR_BUFFER_TOO_SM
                 3: "WLB_ERR_UNSUPPORTED", 4: "WLB_ERR_HIP"}
 
 EXPORTS = ["wlb_last_error", "wlb_pack", "wlb_packer_create", "wlb_packer_destroy", "wlb_packer_step",
-           "wlb_packer_pending", "wlb_calib_mfma", "wlb_shard_size", "wlb_shard", "wlb_attn_workspace_size",
+           "wlb_packer_pending", "wlb_calib_mfma", "wlb_predict_latency", "wlb_select_sharding", "wlb_shard_size", "wlb_shard", "wlb_attn_workspace_size",
            "wlb_attn_plan", "wlb_attn_plan_layout", "wlb_attn_fwd", "wlb_attn_bwd"]
 
 
@@ -121,6 +121,41 @@ def mfma_ceiling(random_operands: bool, n_iter: int = 4000, reps: int = 8) -> fl
     e1.record()
     torch.cuda.synchronize()
     return flops.value * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+class _KernelProfile(C.Structure):
+    _fields_ = [("n_q", C.c_int32), ("n_kv", C.c_int32), ("q_len", C.POINTER(C.c_int32)),
+                ("kv_len", C.POINTER(C.c_int32)), ("tflops", C.POINTER(C.c_double)),
+                ("tile_q", C.c_int32), ("tile_k", C.c_int32)]
+
+
+class KernelProfile:
+    """The profiled-rate table wlb_predict_latency / wlb_select_sharding read (host arrays kept alive here)."""
+
+    def __init__(self, q_grid, kv_grid, tflops, tile_q: int = 128, tile_k: int = 64):
+        self.q = _i32(q_grid)
+        self.kv = _i32(kv_grid)
+        self.t = np.ascontiguousarray(tflops, dtype=np.float64)
+        assert self.t.shape == (len(self.q), len(self.kv))
+        self.c = _KernelProfile(len(self.q), len(self.kv), _np_ptr(self.q, C.c_int32), _np_ptr(self.kv, C.c_int32),
+                                _np_ptr(self.t, C.c_double), tile_q, tile_k)
+
+
+def wlb_predict_latency(doc_len, cp: int, mode: int, hq: int, head_dim: int, profile: KernelProfile):
+    doc_len = _i32(doc_len)
+    out = np.zeros(cp, dtype=np.float64)
+    _check(lib().wlb_predict_latency(_np_ptr(doc_len, C.c_int32), C.c_int64(len(doc_len)), C.c_int32(cp), C.c_int32(mode),
+                                     C.c_int32(hq), C.c_int32(head_dim), C.byref(profile.c), _np_ptr(out, C.c_double)))
+    return out
+
+
+def wlb_select_sharding(doc_len, cp: int, hq: int, head_dim: int, profile: KernelProfile):
+    """-> (mode, predicted latency per-sequence, predicted latency per-document), seconds"""
+    doc_len = _i32(doc_len)
+    mode, a, b = C.c_int32(-1), C.c_double(0.0), C.c_double(0.0)
+    _check(lib().wlb_select_sharding(_np_ptr(doc_len, C.c_int32), C.c_int64(len(doc_len)), C.c_int32(cp), C.c_int32(hq),
+                                     C.c_int32(head_dim), C.byref(profile.c), C.byref(mode), C.byref(a), C.byref(b)))
+    return mode.value, a.value, b.value
 
 
 class Packer:

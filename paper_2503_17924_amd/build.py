@@ -38,7 +38,9 @@ def build(verbose: bool = False, keep_asm: bool = False, lib_out: str | None = N
         obj = os.path.join(bdir, os.path.splitext(src)[0] + ".o")
         cmd = [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         if src.endswith(".cpp"):
-            cmd[1:1] = ["-x", "hip"]
+            # host code: no fused multiply-add contraction, so the latency estimates are the same
+            # doubles on every machine
+            cmd[1:1] = ["-x", "hip", "-ffp-contract=off"]
         if "attn" in src:
             # kernels only: lets max() compile to bare v_max3 (no NaN quieting); the host-side
             # argument checks live in other files and keep full NaN semantics

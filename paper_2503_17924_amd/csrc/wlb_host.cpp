@@ -316,3 +316,107 @@ extern "C" wlb_status wlb_shard(const int32_t* doc_len, int64_t n_docs, int32_t 
     if (useful_pairs) *useful_pairs = pairs;
     return WLB_OK;
 }
+
+// ---------------------------------------------------------------------------------------
+// Adaptive sharding selection (Section 5.3): padded operations / profiled rate per segment,
+// summed per rank, maximum over the ranks of the CP group.  Plain IEEE double arithmetic in a
+// fixed order (this file is compiled without floating-point contraction).
+// ---------------------------------------------------------------------------------------
+namespace {
+
+wlb_status check_profile(const wlb_kernel_profile* t) {
+    if (!t || !t->q_len || !t->kv_len || !t->tflops || t->n_q < 1 || t->n_kv < 1 || t->tile_q < 1 || t->tile_k < 1)
+        return fail(WLB_ERR_INVALID_ARG, "kernel profile: null pointer, empty grid or tile < 1");
+    for (int i = 0; i < t->n_q; ++i)
+        if (t->q_len[i] < 1 || (i > 0 && t->q_len[i] <= t->q_len[i - 1]))
+            return fail(WLB_ERR_INVALID_ARG, "kernel profile: q_len grid must be positive and strictly increasing");
+    for (int i = 0; i < t->n_kv; ++i)
+        if (t->kv_len[i] < 1 || (i > 0 && t->kv_len[i] <= t->kv_len[i - 1]))
+            return fail(WLB_ERR_INVALID_ARG, "kernel profile: kv_len grid must be positive and strictly increasing");
+    for (int64_t i = 0; i < (int64_t)t->n_q * t->n_kv; ++i)
+        if (!(t->tflops[i] > 0.0)) return fail(WLB_ERR_INVALID_ARG, "kernel profile: rates must be positive");
+    return WLB_OK;
+}
+
+int64_t padded_pairs(int64_t q_len, int64_t kv_len, int64_t tile_q, int64_t tile_k) {
+    if (q_len <= 0 || kv_len <= 0) return 0;
+    int64_t total = 0;
+    const int64_t n_tiles = (q_len + tile_q - 1) / tile_q;
+    for (int64_t t = 0; t < n_tiles; ++t) {
+        const int64_t e = std::min((t + 1) * tile_q, q_len);
+        const int64_t vis = kv_len - q_len + e;
+        if (vis <= 0) continue;
+        total += tile_q * ((vis + tile_k - 1) / tile_k * tile_k);
+    }
+    return total;
+}
+
+void bracket(const int32_t* grid, int n, int64_t x, int* i0, int* i1, double* w) {
+    if (x <= grid[0]) { *i0 = *i1 = 0; *w = 0.0; return; }
+    if (x >= grid[n - 1]) { *i0 = *i1 = n - 1; *w = 0.0; return; }
+    int i = 0;
+    while (grid[i + 1] < x) ++i;
+    *i0 = i; *i1 = i + 1;
+    *w = (double)(x - grid[i]) / (double)(grid[i + 1] - grid[i]);
+}
+
+double profile_lookup(const wlb_kernel_profile* t, int64_t q_len, int64_t kv_len) {
+    int i0, i1, j0, j1;
+    double wq, wk;
+    bracket(t->q_len, t->n_q, q_len, &i0, &i1, &wq);
+    bracket(t->kv_len, t->n_kv, kv_len, &j0, &j1, &wk);
+    const double* T = t->tflops;
+    const int nk = t->n_kv;
+    const double top = T[i0 * nk + j0] * (1.0 - wk) + T[i0 * nk + j1] * wk;
+    const double bot = T[i1 * nk + j0] * (1.0 - wk) + T[i1 * nk + j1] * wk;
+    return top * (1.0 - wq) + bot * wq;
+}
+
+wlb_status predict(const int32_t* doc_len, int64_t n_docs, int32_t cp, int32_t mode, int32_t hq, int32_t head_dim,
+                   const wlb_kernel_profile* prof, double* rank_latency) {
+    if (hq < 1 || head_dim < 1) return fail(WLB_ERR_INVALID_ARG, "wlb_predict_latency: hq=%d head_dim=%d", hq, head_dim);
+    if (wlb_status st = check_profile(prof)) return st;
+    const double flops_per_pair = 14.0 * (double)head_dim * (double)hq;
+    for (int32_t r = 0; r < cp; ++r) {
+        ShardArgs a{doc_len, n_docs, cp, r, mode};
+        int64_t total = 0;
+        if (wlb_status st = check_shard(a, &total)) return st;
+        double lat = 0.0;
+        walk_segments(a, total, [&](int64_t, int64_t first, int64_t slots, int64_t real) {
+            const int64_t kv_len = real > 0 ? first + real : 0;
+            const int64_t pairs = padded_pairs(slots, kv_len, prof->tile_q, prof->tile_k);
+            if (pairs == 0) return;
+            const double rate = profile_lookup(prof, slots, kv_len) * 1e12;
+            lat = lat + ((double)pairs * flops_per_pair) / rate;
+        });
+        rank_latency[r] = lat;
+    }
+    return WLB_OK;
+}
+
+}  // namespace
+
+extern "C" wlb_status wlb_predict_latency(const int32_t* doc_len, int64_t n_docs, int32_t cp, int32_t mode, int32_t hq,
+                                          int32_t head_dim, const wlb_kernel_profile* profile, double* rank_latency) {
+    if (!rank_latency || cp < 1) return fail(WLB_ERR_INVALID_ARG, "wlb_predict_latency: null output or cp=%d", cp);
+    return predict(doc_len, n_docs, cp, mode, hq, head_dim, profile, rank_latency);
+}
+
+extern "C" wlb_status wlb_select_sharding(const int32_t* doc_len, int64_t n_docs, int32_t cp, int32_t hq, int32_t head_dim,
+                                          const wlb_kernel_profile* profile, int32_t* mode, double* latency_per_seq,
+                                          double* latency_per_doc) {
+    if (!mode || !latency_per_seq || !latency_per_doc || cp < 1)
+        return fail(WLB_ERR_INVALID_ARG, "wlb_select_sharding: null output or cp=%d", cp);
+    std::vector<double> lat((size_t)cp);
+    double worst[2];
+    const int32_t modes[2] = {WLB_SHARD_PER_SEQ, WLB_SHARD_PER_DOC_PADDED};
+    for (int m = 0; m < 2; ++m) {
+        if (wlb_status st = predict(doc_len, n_docs, cp, modes[m], hq, head_dim, profile, lat.data())) return st;
+        worst[m] = 0.0;
+        for (double x : lat) if (x > worst[m]) worst[m] = x;
+    }
+    *latency_per_seq = worst[0];
+    *latency_per_doc = worst[1];
+    *mode = worst[1] < worst[0] ? WLB_SHARD_PER_DOC_PADDED : WLB_SHARD_PER_SEQ;
+    return WLB_OK;
+}

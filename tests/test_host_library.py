@@ -174,3 +174,36 @@ def test_stream_packer_random_and_errors():
         B.Packer(3, 500, 1, 7, [300, 300])
     with pytest.raises(B.WlbError):
         B.Packer(0, 500, 1, 7)
+
+
+def test_select_sharding_matches_oracle_bit_for_bit():
+    from oracle import select as osel
+    rng = np.random.default_rng(123)
+    q_grid, kv_grid = [16, 128, 1024, 16384], [128, 4096, 131072]
+    for trial in range(25):
+        tab = rng.uniform(5.0, 900.0, size=(4, 3))
+        prof = B.KernelProfile(q_grid, kv_grid, tab)
+        cp = int(rng.choice([1, 2, 4, 8]))
+        n = int(rng.integers(1, 40))
+        doc = rng.integers(1, 5000, size=n)
+        doc[-1] += (-int(doc.sum())) % (2 * cp)           # per-sequence mode needs 2*cp | T
+        hq, d = int(rng.choice([1, 8, 32])), int(rng.choice([64, 128]))
+        for mode in (0, 1, 2):
+            want = [osel.rank_latency(doc.tolist(), cp, r, mode, hq, d, 128, 64, q_grid, kv_grid, tab.tolist())
+                    for r in range(cp)]
+            got = B.wlb_predict_latency(doc, cp, mode, hq, d, prof)
+            assert got.tolist() == want
+        m, a, b = B.wlb_select_sharding(doc, cp, hq, d, prof)
+        assert (m, a, b) == osel.select(doc.tolist(), cp, hq, d, 128, 64, q_grid, kv_grid, tab.tolist())
+
+
+def test_select_sharding_hand_example_and_errors():
+    prof = B.KernelProfile([2, 8], [8, 32], [[1000e-12, 2000e-12], [2000e-12, 4000e-12]], tile_q=4, tile_k=4)
+    m, a, b = B.wlb_select_sharding([8, 24], 2, 1, 1, prof)
+    assert m == B.SHARD_PER_SEQ and abs(a - 1.0752) < 1e-6 and abs(b - 2.217035) < 1e-5
+    with pytest.raises(B.WlbError):
+        B.wlb_select_sharding([8, 23], 2, 1, 1, prof)                     # per-sequence needs 4 | T
+    with pytest.raises(B.WlbError):
+        B.wlb_select_sharding([8, 24], 2, 1, 1, B.KernelProfile([8, 2], [8, 32], [[1, 1], [1, 1]]))
+    with pytest.raises(B.WlbError):
+        B.wlb_select_sharding([8, 24], 2, 1, 1, B.KernelProfile([2, 8], [8, 32], [[1, 0], [1, 1]]))
