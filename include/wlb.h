@@ -68,6 +68,21 @@ wlb_status wlb_pack(const int32_t* doc_len, int64_t n_docs,
                     int32_t* assign, int64_t* mb_len, uint64_t* mb_cost);
 
 /* ------------------------------------------------------------------------------------------
+ * Exact solution of Equation 2 (Section 4.1) for small inputs, by branch and bound: every
+ * document in exactly one micro-batch, every micro-batch at most l_max tokens, the largest
+ * micro-batch cost (cost as in wlb_pack) minimal.  The paper solves this with an ILP solver
+ * and reports it too slow for training (Section 4.1, Table 2); here it measures how far the
+ * greedy of wlb_pack is from the optimum on small instances.  Host, synchronous.
+ * node_limit > 0 bounds the search (nodes visited); *proven = 1 when the search finished, 0 when
+ * the limit cut it short (the result is then the best assignment found).  Outputs as wlb_pack,
+ * without -1 entries.  Errors: INVALID_ARG (null pointers, n_docs or n_microbatch outside
+ * 1..64, a length outside (0, l_max], cost overflow, no feasible assignment found).
+ */
+wlb_status wlb_pack_optimal(const int32_t* doc_len, int64_t n_docs, int32_t n_microbatch, int64_t l_max,
+                            uint64_t cost_a, uint64_t cost_b, int64_t node_limit, int32_t* assign,
+                            int64_t* mb_len, uint64_t* mb_cost, uint64_t* optimal_cost, int32_t* proven);
+
+/* ------------------------------------------------------------------------------------------
  * Streaming packer -- the whole of Algorithm 1 (Section 4.3) including the outlier delay of
  * Section 4.2, one step per global batch.  The packer object lives in host memory and carries
  * the algorithm's state between steps: the left-over documents and the FIFO waiting queues.

@@ -66,6 +66,28 @@ def pack(doc_len, n_microbatch: int, l_max: int, a: int, b: int):
     return assign, length, work
 
 
+def pack_optimal_bruteforce(doc_len, n_microbatch: int, l_max: int, a: int, b: int):
+    """Equation 2 by exhaustive search (Section 4.1): every document in exactly one micro-batch,
+    every micro-batch at most l_max tokens, minimise the largest micro-batch cost.  Returns the
+    optimal value, or None when no assignment satisfies the length limit.  Exponential: tiny
+    inputs only (it tries all n_microbatch^n assignments, nothing pruned, so that it stays an
+    independent check of the library's branch-and-bound solver)."""
+    import itertools
+    doc_len = [int(x) for x in doc_len]
+    best = None
+    for assign in itertools.product(range(n_microbatch), repeat=len(doc_len)):
+        length = [0] * n_microbatch
+        work = [0] * n_microbatch
+        for d, j in zip(doc_len, assign):
+            length[j] += d
+            work[j] += cost(d, a, b)
+        if max(length) <= l_max:
+            w = max(work)
+            if best is None or w < best:
+                best = w
+    return best
+
+
 def pack_stream(batches, n_microbatch: int, l_max: int, a: int, b: int):
     """batches: iterable of lists of document lengths (one list per global batch).
     Returns a list with one entry per iteration: (doc_lengths_considered, assign,

@@ -29,7 +29,7 @@ ATTN_BWD_SKIP_DKV = 8
 STATUS_NAMES = {0: "WLB_OK", 1: "WLB_ERR_INVALID_ARG", 2: "WLB_ERR_BUFFER_TOO_SMALL",
                 3: "WLB_ERR_UNSUPPORTED", 4: "WLB_ERR_HIP"}
 
-EXPORTS = ["wlb_last_error", "wlb_pack", "wlb_packer_create", "wlb_packer_destroy", "wlb_packer_step",
+EXPORTS = ["wlb_last_error", "wlb_pack", "wlb_pack_optimal", "wlb_packer_create", "wlb_packer_destroy", "wlb_packer_step",
            "wlb_packer_pending", "wlb_calib_mfma", "wlb_predict_latency", "wlb_select_sharding", "wlb_shard_size", "wlb_shard", "wlb_attn_workspace_size",
            "wlb_attn_plan", "wlb_attn_plan_layout", "wlb_attn_fwd", "wlb_attn_bwd"]
 
@@ -121,6 +121,20 @@ def mfma_ceiling(random_operands: bool, n_iter: int = 4000, reps: int = 8) -> fl
     e1.record()
     torch.cuda.synchronize()
     return flops.value * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+def wlb_pack_optimal(doc_len, n_microbatch: int, l_max: int, cost_a: int, cost_b: int, node_limit: int = 0):
+    """-> (assign, mb_len, mb_cost, optimal_cost, proven)"""
+    doc_len = _i32(doc_len)
+    assign = np.empty(len(doc_len), dtype=np.int32)
+    mb_len = np.empty(n_microbatch, dtype=np.int64)
+    mb_cost = np.empty(n_microbatch, dtype=np.uint64)
+    opt, proven = C.c_uint64(0), C.c_int32(0)
+    _check(lib().wlb_pack_optimal(_np_ptr(doc_len, C.c_int32), C.c_int64(len(doc_len)), C.c_int32(n_microbatch),
+                                  C.c_int64(l_max), C.c_uint64(cost_a), C.c_uint64(cost_b), C.c_int64(node_limit),
+                                  _np_ptr(assign, C.c_int32), _np_ptr(mb_len, C.c_int64), _np_ptr(mb_cost, C.c_uint64),
+                                  C.byref(opt), C.byref(proven)))
+    return assign, mb_len, mb_cost, opt.value, bool(proven.value)
 
 
 class _KernelProfile(C.Structure):

@@ -420,3 +420,89 @@ extern "C" wlb_status wlb_select_sharding(const int32_t* doc_len, int64_t n_docs
     *mode = worst[1] < worst[0] ? WLB_SHARD_PER_DOC_PADDED : WLB_SHARD_PER_SEQ;
     return WLB_OK;
 }
+
+// ---------------------------------------------------------------------------------------
+// Exact solution of Equation 2 (Section 4.1) for small inputs: depth-first branch and bound over
+// the documents in descending length.  A branch is cut when its largest micro-batch cost cannot
+// beat the best complete assignment; micro-batches that are still empty are interchangeable, so
+// only the first of them is tried.
+// ---------------------------------------------------------------------------------------
+namespace {
+
+struct OptSearch {
+    int n, nb;
+    int64_t l_max;
+    std::vector<int64_t> len;       // documents, descending
+    std::vector<uint64_t> cst;
+    std::vector<int64_t> bin_len;
+    std::vector<uint64_t> bin_cost;
+    std::vector<int> cur, best_assign;
+    uint64_t best = std::numeric_limits<uint64_t>::max();
+    bool found = false;
+    int64_t nodes = 0, node_limit;
+
+    void go(int i, uint64_t cur_max) {
+        if (node_limit > 0 && nodes >= node_limit) return;
+        ++nodes;
+        if (i == n) {
+            if (!found || cur_max < best) { best = cur_max; best_assign = cur; found = true; }
+            return;
+        }
+        bool tried_empty = false;
+        for (int j = 0; j < nb; ++j) {
+            if (bin_len[j] == 0) { if (tried_empty) continue; tried_empty = true; }
+            if (bin_len[j] + len[i] > l_max) continue;
+            const uint64_t c = bin_cost[j] + cst[i];
+            const uint64_t m = std::max(cur_max, c);
+            if (found && m >= best) continue;
+            bin_len[j] += len[i]; bin_cost[j] = c; cur[i] = j;
+            go(i + 1, m);
+            bin_len[j] -= len[i]; bin_cost[j] = c - cst[i];
+        }
+    }
+};
+
+}  // namespace
+
+extern "C" wlb_status wlb_pack_optimal(const int32_t* doc_len, int64_t n_docs, int32_t n_microbatch, int64_t l_max,
+                                       uint64_t cost_a, uint64_t cost_b, int64_t node_limit, int32_t* assign,
+                                       int64_t* mb_len, uint64_t* mb_cost, uint64_t* optimal_cost, int32_t* proven) {
+    if (!doc_len || !assign || !mb_len || !mb_cost || !optimal_cost || !proven)
+        return fail(WLB_ERR_INVALID_ARG, "wlb_pack_optimal: null pointer");
+    if (n_docs < 1 || n_docs > 64 || n_microbatch < 1 || n_microbatch > 64 || l_max < 1)
+        return fail(WLB_ERR_INVALID_ARG, "wlb_pack_optimal: n_docs=%lld (1..64) n_microbatch=%d (1..64) l_max=%lld",
+                    (long long)n_docs, n_microbatch, (long long)l_max);
+    if (!cost_fits(cost_a, cost_b, l_max))
+        return fail(WLB_ERR_INVALID_ARG, "wlb_pack_optimal: cost_a*l_max^2 + cost_b*l_max overflows 64 bits");
+    for (int64_t i = 0; i < n_docs; ++i)
+        if (doc_len[i] <= 0 || doc_len[i] > l_max)
+            return fail(WLB_ERR_INVALID_ARG, "wlb_pack_optimal: doc_len[%lld]=%d outside (0, l_max]", (long long)i, doc_len[i]);
+    std::vector<int> order((size_t)n_docs);
+    for (int i = 0; i < (int)n_docs; ++i) order[(size_t)i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return doc_len[x] > doc_len[y]; });
+    OptSearch s;
+    s.n = (int)n_docs; s.nb = n_microbatch; s.l_max = l_max; s.node_limit = node_limit;
+    for (int i : order) {
+        const uint64_t d = (uint64_t)doc_len[i];
+        s.len.push_back(doc_len[i]);
+        s.cst.push_back(cost_a * d * d + cost_b * d);
+    }
+    s.bin_len.assign((size_t)n_microbatch, 0);
+    s.bin_cost.assign((size_t)n_microbatch, 0);
+    s.cur.assign((size_t)n_docs, -1);
+    s.go(0, 0);
+    if (!s.found)
+        return fail(WLB_ERR_INVALID_ARG, s.node_limit > 0 && s.nodes >= s.node_limit
+                        ? "wlb_pack_optimal: node limit reached before any complete assignment"
+                        : "wlb_pack_optimal: no assignment keeps every micro-batch within l_max");
+    for (int j = 0; j < n_microbatch; ++j) { mb_len[j] = 0; mb_cost[j] = 0; }
+    for (int k = 0; k < (int)n_docs; ++k) {
+        const int i = order[(size_t)k], j = s.best_assign[(size_t)k];
+        assign[i] = j;
+        mb_len[j] += s.len[(size_t)k];
+        mb_cost[j] += s.cst[(size_t)k];
+    }
+    *optimal_cost = s.best;
+    *proven = !(s.node_limit > 0 && s.nodes >= s.node_limit);
+    return WLB_OK;
+}

@@ -165,6 +165,12 @@ def config(idx: int) -> Workload:
         return Workload("c4_straggler", straggler_docs(4, 131072, 98304, 1, 64), 131072,
                         hq=16, hkv=2, head_dim=128, scale=1.0 / math.sqrt(128.0), cp=4,
                         backward=True, tensor_seed=1004)
+    if idx == 5:
+        # a second context window: the 64K setting of the paper's evaluation (Section 6.1, model and
+        # parallelism table), one TP=4 share of a 7B-class layer (multi-head attention), CP=2
+        return Workload("c5_64k_mha_cp2", mixture_docs_fill(5, 65536, 8192, 65536), 65536,
+                        hq=8, hkv=8, head_dim=128, scale=1.0 / math.sqrt(128.0), cp=2,
+                        backward=True, tensor_seed=1005)
     raise ValueError(f"no config {idx}")
 
 

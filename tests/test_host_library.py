@@ -207,3 +207,41 @@ def test_select_sharding_hand_example_and_errors():
         B.wlb_select_sharding([8, 24], 2, 1, 1, B.KernelProfile([8, 2], [8, 32], [[1, 1], [1, 1]]))
     with pytest.raises(B.WlbError):
         B.wlb_select_sharding([8, 24], 2, 1, 1, B.KernelProfile([2, 8], [8, 32], [[1, 0], [1, 1]]))
+
+
+def test_pack_optimal_matches_exhaustive_search_and_bounds_the_greedy():
+    rng = np.random.default_rng(2024)
+    gaps = []
+    for trial in range(60):
+        n, nb = int(rng.integers(1, 9)), int(rng.integers(1, 4))
+        doc = rng.integers(1, 200, size=n)
+        l_max = int(max(doc.max(), rng.integers(int(doc.sum()) // nb + 1, int(doc.sum()) + 2)))
+        a, b = int(rng.integers(0, 4)), int(rng.integers(0, 500))
+        want = opk.pack_optimal_bruteforce(doc.tolist(), nb, l_max, a, b)
+        if want is None:
+            with pytest.raises(B.WlbError):
+                B.wlb_pack_optimal(doc, nb, l_max, a, b)
+            continue
+        assign, mb_len, mb_cost, opt, proven = B.wlb_pack_optimal(doc, nb, l_max, a, b)
+        assert proven and opt == want
+        # the returned assignment is feasible and attains the optimum
+        for j in range(nb):
+            sel = doc[assign == j]
+            assert int(sel.sum()) == mb_len[j] <= l_max
+            assert sum(opk.cost(int(d), a, b) for d in sel) == mb_cost[j]
+        assert set(assign.tolist()) <= set(range(nb)) and int(mb_cost.max()) == opt
+        g_assign, _, g_cost = B.wlb_pack(doc, nb, l_max, a, b)
+        if (g_assign >= 0).all():
+            assert int(g_cost.max()) >= opt
+            gaps.append(int(g_cost.max()) / max(opt, 1))
+    assert gaps and max(gaps) < 1.5
+
+
+def test_pack_optimal_node_limit_and_errors():
+    doc = np.arange(40, 0, -1, dtype=np.int32) * 37
+    assign, mb_len, mb_cost, opt, proven = B.wlb_pack_optimal(doc, 8, 131072, 6, 640000, node_limit=20000)
+    assert not proven and (assign >= 0).all() and int(mb_cost.max()) == opt
+    with pytest.raises(B.WlbError):
+        B.wlb_pack_optimal(np.ones(65, dtype=np.int32), 2, 100, 1, 1)
+    with pytest.raises(B.WlbError):
+        B.wlb_pack_optimal([60, 60, 60], 2, 100, 1, 1)          # three documents of 60 cannot share two bins of 100

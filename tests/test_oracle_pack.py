@@ -220,3 +220,16 @@ def test_outlier_delay_improves_balance_on_the_long_tailed_pool():
     two_q = run([window // 2, window * 3 // 4])
     assert plain < fixed
     assert two_q < plain
+
+
+def test_exhaustive_optimum_on_textbook_partition_instances():
+    # linear cost (a=0, b=1) without a binding length limit is multiway number partitioning
+    assert opk.pack_optimal_bruteforce([3, 3, 2, 2, 2], 2, 100, 0, 1) == 6          # {3,3} | {2,2,2}; LPT gives 7
+    assert opk.pack_optimal_bruteforce([8, 7, 6, 5, 4], 2, 100, 0, 1) == 15         # {8,7} | {6,5,4}
+    assert opk.pack_optimal_bruteforce([5, 5, 5, 5], 2, 10, 0, 1) == 10
+    assert opk.pack_optimal_bruteforce([5, 5, 5, 5], 2, 9, 0, 1) is None            # the length limit makes it infeasible
+    assert opk.pack_optimal_bruteforce([3, 2, 2], 2, 100, 1, 0) == 9                # quadratic cost: {3} | {2,2} = max(9, 8)
+    # the length limit can force a worse optimum: {4,1} | {3,2} is forbidden when l_max = 4... so is everything
+    assert opk.pack_optimal_bruteforce([4, 3, 2, 1], 2, 5, 0, 1) == 5
+    # greedy LPT on the first instance is strictly worse than the optimum
+    assert max(opk.pack([3, 3, 2, 2, 2], 2, 100, 0, 1)[2]) == 7
