@@ -83,7 +83,7 @@ def main():
     device = torch.device("cuda:0")
     w = wl.config(args.config)
     if args.config == 3:
-        raise SystemExit("config 3 (packing pool) is covered by tests; bench configs: 1, 2, 4")
+        raise SystemExit("config 3 (packing pool) is covered by tests; bench configs: 1, 2, 4, 5")
     D, hq = w.head_dim, w.hq
 
     t0 = time.time()

@@ -110,6 +110,25 @@ def test_config2_128k_cp8_rank(rank, mode):
     _check_identities(c, dq, dk, dv)
 
 
+@pytest.mark.parametrize("rank,mode", [(1, B.SHARD_PER_DOC_PADDED), (0, B.SHARD_PER_DOC_NOPAD)])
+def test_config5_64k_mha_cp2_rank(rank, mode):
+    # the 64K context window of the paper's evaluation (Section 6.1), multi-head attention (hq = hkv = 8)
+    w, c = _full_size_case(5, rank, mode)
+    o, lse = c.run_fwd()
+    dq, dk, dv = c.run_bwd()
+    rows = _rows_sample(c.q_idx, c.cu_k, 24, np.random.default_rng(50 + rank))
+    _check_rows(c, o, lse, dq, rows, f"c5 rank {rank}")
+    cu = c.cu_k
+    real = np.nonzero(c.q_idx >= 0)[0]
+    doc = np.searchsorted(cu, c.q_idx[real], side="right") - 1
+    checked = 0
+    for d in np.unique(doc):
+        if cu[d + 1] - cu[d] <= 1024 and checked < 12:
+            _check_dkv_for_rows(c, dk, dv, real[doc == d], cu[d], cu[d + 1], f"document {d}")
+            checked += 1
+    _check_identities(c, dq, dk, dv)
+
+
 def test_config1_32k_gqa():
     w, c = _full_size_case(1, 0, B.SHARD_PER_DOC_PADDED)
     o, lse = c.run_fwd()
