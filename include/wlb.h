@@ -222,6 +222,13 @@ typedef struct {
     size_t  off_fwd_cost;                /* int32 [n_fwd_tiles]: key tiles each query tile visits */
     size_t  off_key_order;               /* int32 [n_key_tiles] */
     size_t  off_key_range;               /* int32 [n_key_tiles][2]: first, one-past-last group that can see the tile */
+    /* dK/dV work items: a key tile whose work (groups in its range x query heads of a KV head) exceeds
+       a threshold is split by heads into 2, 4 or 8 items that write fp32 partial results; tiles are
+       ordered by item cost, heaviest first (off_key_order), and a tile's items are consecutive */
+    int32_t dkv_max_items, dkv_max_partials;   /* upper bounds used for the launch and the workspace */
+    size_t  off_key_ways;                /* int32 [n_key_tiles]: items per (key tile, KV head), by key tile */
+    size_t  off_key_item_base;           /* int32 [n_key_tiles + 1]: first item of the tile of order rank r */
+    size_t  off_key_slot_base;           /* int32 [n_key_tiles + 1]: first partial slot of the tile of rank r */
     size_t  plan_bytes;
 } wlb_plan_layout;
 

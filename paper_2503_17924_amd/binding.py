@@ -50,7 +50,9 @@ class PlanLayout(C.Structure):
                 ("n_fwd_tiles", C.c_int32), ("bwd_key_tile", C.c_int32), ("n_key_tiles", C.c_int32),
                 ("off_row_lo", C.c_size_t), ("off_row_hi", C.c_size_t), ("off_group", C.c_size_t),
                 ("off_group_real", C.c_size_t), ("off_fwd_order", C.c_size_t), ("off_fwd_cost", C.c_size_t), ("off_key_order", C.c_size_t),
-                ("off_key_range", C.c_size_t), ("plan_bytes", C.c_size_t)]
+                ("off_key_range", C.c_size_t), ("dkv_max_items", C.c_int32), ("dkv_max_partials", C.c_int32),
+                ("off_key_ways", C.c_size_t), ("off_key_item_base", C.c_size_t), ("off_key_slot_base", C.c_size_t),
+                ("plan_bytes", C.c_size_t)]
 
 
 _lib = None

@@ -33,6 +33,8 @@ struct BwdParams {
     __bf16* dq; __bf16* dk; __bf16* dv;
     const int32_t* row_lo; const int32_t* row_hi; const int32_t* group; const int32_t* group_real;
     const int32_t* fwd_order; const int32_t* key_order; const int32_t* key_range;
+    const int32_t* key_ways; const int32_t* key_item_base; const int32_t* key_slot_base;
+    float* partial;
     int n_q, t_kv, hq, hkv, n_groups, n_tiles, n_key_tiles;
     float scale_log2e, scale;
 };
@@ -265,14 +267,24 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
     __shared__ __attribute__((aligned(16))) int hi_s[2][GR];
 
     const int G = p.hq / p.hkv;
-    const int x = blockIdx.x & 7;
-    const int y = blockIdx.x >> 3;
-    const int hk = y % p.hkv;
-    const int c = y / p.hkv;
-    const int rank = c * 8 + x;
-    if (rank >= p.n_key_tiles) return;
-    const int kt = p.key_order[rank];
-    const int k0 = kt * BNK;
+    // Work item blockIdx.x: tiles in order (heaviest item first), a tile's items consecutive:
+    // KV head major, head part minor.  Consecutive items run on consecutive XCDs, so the same head
+    // part of neighbouring tiles shares an XCD (and its L2 copy of the Q / dO tiles).
+    const int n_items = ld_const(p.key_item_base + p.n_key_tiles);
+    if ((int)blockIdx.x >= n_items) return;
+    int r = 0;
+    for (int hi = p.n_key_tiles; hi - r > 1;) {
+        const int mid = (r + hi) >> 1;
+        if (ld_const(p.key_item_base + mid) <= (int)blockIdx.x) r = mid; else hi = mid;
+    }
+    const int kt = ld_const(p.key_order + r);
+    const int ways = ld_const(p.key_ways + kt);
+    const int j = (int)blockIdx.x - ld_const(p.key_item_base + r);
+    const int hk = j / ways, part = j % ways;
+    const int nh = G / ways;                 // query heads of this item: hk * G + part * nh + [0, nh)
+    const int h_first = hk * G + part * nh;
+    const bool whole = ways == 1;
+    const int slot = ld_const(p.key_slot_base + r) + j;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
     // role and key block are left as per-lane values: as scalars they raise the register pressure
@@ -280,33 +292,7 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
     const int role = tid >> 8, kblk = (tid >> 6) & 3;
     const int l32 = lane & 31, half = lane >> 5;
     const int j16 = lane & 15, gi = (lane >> 4) & 1;
-    const int kw0 = k0 + kblk * 32;
-    const int mykey = kw0 + l32;
-
-    // this wavefront's B operands: K rows (score role) or V rows (gradient role) of its 32 keys
-    bf16x8 bop[KS];
-    {
-        const int kr = min(mykey, p.t_kv - 1);
-        const __bf16* src = (role == 0 ? p.k : p.v) + ((size_t)kr * p.hkv + hk) * D + half * 8;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) bop[ks] = *reinterpret_cast<const bf16x8*>(src + ks * 16);
-    }
-    f32x16 acc[DB];     // dV^T (score role) or dK^T (gradient role)
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
-
     const float cs = p.scale_log2e;
-    const int g_end = p.key_range[2 * kt + 1];
-    const int k1 = min(k0 + BNK, p.t_kv);
-    auto next_group = [&](int g) {
-        for (; g < g_end; ++g) {
-            const int4 gd = reinterpret_cast<const int4*>(p.group)[g];
-            if (gd.y > gd.x && gd.x < k1 && gd.y > k0) break;
-        }
-        return g;
-    };
 
     const uint32_t q_row = (uint32_t)p.hq * D;
     const uint32_t q_total = (uint32_t)p.n_q * q_row * 2u;
@@ -361,25 +347,61 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
         }
     const uint32_t pbuf_lane = (uint32_t)(uintptr_t)(WLB_LDS char*)pbuf + kblk * 4096 + lane * 16;
 
-    int g = next_group(p.key_range[2 * kt]);
-    int hh = 0, buf = 0;
-    if (g < g_end) {
-        issue_stage(g, hk * G, 0);
-        load_small(g, hk * G, 0);
+    // stage t of the item is row group g_first + t / nh with query head h_first + t % nh; every
+    // group of the tile's range is a stage (one whose hull misses the tile, rare, costs a copy and no math)
+    const int g_first = ld_const(p.key_range + 2 * kt);
+    const int t1 = (ld_const(p.key_range + 2 * kt + 1) - g_first) * nh;
+    int buf = 0;
+    const int k0 = kt * BNK;
+    const int kw0 = k0 + kblk * 32;
+    const int mykey = kw0 + l32;
+
+    // this wavefront's B operands: K rows (score role) or V rows (gradient role) of its 32 keys
+    bf16x8 bop[KS];
+    {
+        const int kr = min(mykey, p.t_kv - 1);
+        const __bf16* src = (role == 0 ? p.k : p.v) + ((size_t)kr * p.hkv + hk) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) bop[ks] = *reinterpret_cast<const bf16x8*>(src + ks * 16);
     }
-    while (g < g_end) {
-        int gn = g, hn = hh + 1;
-        if (hn == G) { hn = 0; gn = next_group(g + 1); }
-        const int4 gd = reinterpret_cast<const int4*>(p.group)[g];
-        const bool full = (gd.z <= k0) && (k0 + BNK <= gd.w);
-        const bool wave_live = (gd.x < kw0 + 32) && (gd.y > kw0);
-        const bool has_pads = p.group_real[g] < min(GR, p.n_q - g * GR);
+    f32x16 acc[DB];     // dV^T (score role) or dK^T (gradient role)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+
+    // The schedule data of a stage (its group's hull, fully visible range and real-row count) comes
+    // by scalar loads issued one stage ahead, just before the mid-stage barrier, and is turned into
+    // the next stage's flags right after it: a load at the top of a stage would put its whole
+    // latency in front of the stage's first barrier.
+    struct Flags { bool full, live, pads; };
+    auto flags_of = [&](const int4& gd, int real, int g) {
+        Flags f;
+        f.full = (gd.z <= k0) && (k0 + BNK <= gd.w);
+        f.live = (gd.x < kw0 + 32) && (gd.y > kw0);
+        f.pads = real < min(GR, p.n_q - g * GR);
+        return f;
+    };
+    int t = 0;
+    Flags cur_f{false, false, false};
+    if (t < t1) {
+        cur_f = flags_of(ld_const4(p.group + 4 * g_first), ld_const(p.group_real + g_first), g_first);
+        issue_stage(g_first, h_first, buf);
+        load_small(g_first, h_first, buf);
+    }
+    // no compiler-visible vector load may be pending inside the stage loop (it would wait for the copies too)
+    wait_vmem();
+    while (t < t1) {
+        const int g = g_first + t / nh;
+        const int tn = t + 1;
+        const int gn = g_first + tn / nh, hn = tn % nh;
+        const bool full = cur_f.full, wave_live = cur_f.live, has_pads = cur_f.pads;
 
         wait_vmem();
         __syncthreads();      // barrier 1: stage (g, hh) is in LDS; everyone has left the other buffers and pbuf
-        if (gn < g_end) {
-            issue_stage(gn, hk * G + hn, buf ^ 1);
-            load_small(gn, hk * G + hn, buf ^ 1);
+        if (tn < t1) {
+            issue_stage(gn, h_first + hn, buf ^ 1);
+            load_small(gn, h_first + hn, buf ^ 1);
         }
         if (has_pads) {
             const int r = tid >> 3, part = tid & 7;       // 512 threads: 8 per row
@@ -468,7 +490,12 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
                 }
             }
         }
+        int4 gd_n = int4{0, 0, 0, 0};
+        int real_n = 0;
+        const bool new_group = tn < t1 && gn != g;
+        if (new_group) { gd_n = ld_const4(p.group + 4 * gn); real_n = ld_const(p.group_real + gn); }
         __syncthreads();      // barrier 2: P of this stage is visible to the partners
+        if (new_group) cur_f = flags_of(gd_n, real_n, gn);
 
         // ---------------- phase 2
         if (wave_live) {
@@ -530,20 +557,59 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
                 }
             }
         }
-        g = gn; hh = hn; buf ^= 1;
+        t = tn; buf ^= 1;
     }
 
-    if (mykey < p.t_kv) {
-        __bf16* op = (role == 0 ? p.dv : p.dk) + ((size_t)mykey * p.hkv + hk) * D;
-        const float f = role == 0 ? 1.0f : p.scale;
+    if (whole) {
+        if (mykey < p.t_kv) {
+            __bf16* op = (role == 0 ? p.dv : p.dk) + ((size_t)mykey * p.hkv + hk) * D;
+            const float f = role == 0 ? 1.0f : p.scale;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int d = db * 32 + r4 * 8 + half * 4;
+                    *reinterpret_cast<bf16x4*>(op + d) = pack4(acc[db][r4 * 4 + 0] * f, acc[db][r4 * 4 + 1] * f,
+                                                               acc[db][r4 * 4 + 2] * f, acc[db][r4 * 4 + 3] * f);
+                }
+        }
+    } else {
+        // part of a key tile's work: unscaled fp32 partial [dK | dV][key][d], summed by dkv_fixup_kernel
+        float* op = p.partial + (size_t)slot * (2 * BNK * D) + (role == 0 ? BNK * D : 0) + (size_t)(kblk * 32 + l32) * D;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
                 const int d = db * 32 + r4 * 8 + half * 4;
-                *reinterpret_cast<bf16x4*>(op + d) = pack4(acc[db][r4 * 4 + 0] * f, acc[db][r4 * 4 + 1] * f,
-                                                           acc[db][r4 * 4 + 2] * f, acc[db][r4 * 4 + 3] * f);
+                *reinterpret_cast<f32x4*>(op + d) = f32x4{acc[db][r4 * 4 + 0], acc[db][r4 * 4 + 1],
+                                                          acc[db][r4 * 4 + 2], acc[db][r4 * 4 + 3]};
             }
+    }
+}
+
+// Sums the partial results of the key tiles that were split into several items.
+// One workgroup per (tile in order, KV head).
+template <int D>
+__global__ void __launch_bounds__(256) dkv_fixup_kernel(const BwdParams p) {
+    constexpr int BNK = kBwdKeyTile;
+    const int hk = blockIdx.x % p.hkv, r = blockIdx.x / p.hkv;
+    const int kt = p.key_order[r];
+    const int ways = p.key_ways[kt];
+    if (ways == 1) return;                      // one item did the whole tile and wrote dK/dV itself
+    const int k0 = kt * BNK, nk = min(BNK, p.t_kv - k0);
+    const float* src = p.partial + (size_t)(p.key_slot_base[r] + hk * ways) * (2 * BNK * D);
+    constexpr int V4 = D / 4;                   // float4 per row
+    for (int e = threadIdx.x; e < 2 * BNK * V4; e += 256) {
+        const int which = e / (BNK * V4), rem = e % (BNK * V4);
+        const int key = rem / V4, d4 = rem % V4;
+        if (key >= nk) continue;
+        f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < ways; ++i)
+                sum += *reinterpret_cast<const f32x4*>(src + (size_t)i * (2 * BNK * D) + (size_t)which * BNK * D +
+                                                       (size_t)key * D + d4 * 4);
+        const float f = which == 0 ? p.scale : 1.0f;
+        __bf16* op = (which == 0 ? p.dk : p.dv) + ((size_t)(k0 + key) * p.hkv + hk) * D + d4 * 4;
+        *reinterpret_cast<bf16x4*>(op) = pack4(sum[0] * f, sum[1] * f, sum[2] * f, sum[3] * f);
     }
 }
 
@@ -564,6 +630,10 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.fwd_order = (const int32_t*)(ws + L.off_fwd_order);
     p.key_order = (const int32_t*)(ws + L.off_key_order);
     p.key_range = (const int32_t*)(ws + L.off_key_range);
+    p.key_ways = (const int32_t*)(ws + L.off_key_ways);
+    p.key_item_base = (const int32_t*)(ws + L.off_key_item_base);
+    p.key_slot_base = (const int32_t*)(ws + L.off_key_slot_base);
+    p.partial = (float*)(ws + off_delta + 2 * align_up(sizeof(float) * (size_t)d.hq * d.n_q, 256));
     p.n_q = d.n_q; p.t_kv = d.t_kv; p.hq = d.hq; p.hkv = d.hkv;
     p.n_groups = L.n_groups; p.n_tiles = L.n_fwd_tiles; p.n_key_tiles = L.n_key_tiles;
     p.scale = d.scale;
@@ -572,18 +642,25 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     const size_t n_lanes = (size_t)d.n_q * d.hq * (d.head_dim / 8);
     const unsigned grid_delta = (unsigned)((n_lanes + 255) / 256);
     const unsigned grid_dq = (unsigned)((L.n_fwd_tiles + 7) / 8) * 8u * (unsigned)d.hq;
-    const unsigned grid_dkv = (unsigned)((L.n_key_tiles + 7) / 8) * 8u * (unsigned)d.hkv;
+    const unsigned grid_dkv = (unsigned)L.dkv_max_items;         // items past the actual count exit at once
+    const unsigned grid_fix = (unsigned)(L.n_key_tiles * d.hkv);
     const bool do_delta = !(d.flags & WLB_ATTN_BWD_SKIP_DELTA);
     const bool do_dq = !(d.flags & WLB_ATTN_BWD_SKIP_DQ);
     const bool do_dkv = !(d.flags & WLB_ATTN_BWD_SKIP_DKV);
     if (d.head_dim == 128) {
         if (do_delta) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p);
         if (do_dq) dq_kernel<128><<<grid_dq, 256, 0, stream>>>(p);
-        if (do_dkv) dkv_kernel<128><<<grid_dkv, 512, 0, stream>>>(p);
+        if (do_dkv) {
+            dkv_kernel<128><<<grid_dkv, 512, 0, stream>>>(p);
+            dkv_fixup_kernel<128><<<grid_fix, 256, 0, stream>>>(p);
+        }
     } else {
         if (do_delta) delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p);
         if (do_dq) dq_kernel<64><<<grid_dq, 256, 0, stream>>>(p);
-        if (do_dkv) dkv_kernel<64><<<grid_dkv, 512, 0, stream>>>(p);
+        if (do_dkv) {
+            dkv_kernel<64><<<grid_dkv, 512, 0, stream>>>(p);
+            dkv_fixup_kernel<64><<<grid_fix, 256, 0, stream>>>(p);
+        }
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(WLB_ERR_HIP, "backward launch: %s", hipGetErrorString(e));

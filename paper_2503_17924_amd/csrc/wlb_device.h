@@ -70,6 +70,18 @@ __device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3) 
 __device__ __forceinline__ uint32_t uniform(uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); }
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Loads through the constant address space: with a wave-uniform address they become scalar
+// loads (counted by lgkmcnt, not vmcnt, so they do not interfere with the asynchronous tile
+// copies).  Only for data no kernel writes while this one runs (the schedule tables).
+#define WLB_CONST __attribute__((address_space(4)))
+__device__ __forceinline__ int ld_const(const int32_t* p) {
+    return *reinterpret_cast<const WLB_CONST int*>((uintptr_t)p);
+}
+__device__ __forceinline__ int4 ld_const4(const int32_t* p) {
+    const i32x4 v = *reinterpret_cast<const WLB_CONST i32x4*>((uintptr_t)p);
+    return int4{v[0], v[1], v[2], v[3]};
+}
+
 // XOR swizzle of the 16-byte chunks of an unpadded row-major LDS tile whose rows hold CPR
 // chunks: logical chunk cc of row r is stored at chunk swz(r, cc).  With 256-byte rows it
 // makes both access patterns of the kernels bank-conflict free: 16 rows x one chunk (b128

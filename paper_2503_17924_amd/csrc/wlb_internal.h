@@ -17,6 +17,14 @@ constexpr int kBwdKeyTile = 128;  // keys per dK/dV work item
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+constexpr int kLists = 8;         // XCDs: workgroup b runs on XCD b % 8
+constexpr int kDkvSplit = 8;      // a dK/dV item is at most 1/kDkvSplit of the mean load of a compute unit
+
+// compute units of the GPU (256 when none is present: layout queries on the host)
+int compute_units();
+// bytes of the dK/dV partial results that follow delta / lse2 in the backward workspace
+size_t dkv_partial_bytes(const wlb_attn_desc& d, const wlb_plan_layout& L);
+
 // Validates desc; on success fills the plan layout.
 wlb_status check_desc(const wlb_attn_desc* d);
 void plan_layout(const wlb_attn_desc& d, wlb_plan_layout* L);

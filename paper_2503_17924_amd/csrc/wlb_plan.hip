@@ -34,6 +34,23 @@ wlb_status check_desc(const wlb_attn_desc* d) {
     return WLB_OK;
 }
 
+int compute_units() {
+    static int cached = 0;          // the library runs on one kind of GPU per process
+    if (cached == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            cus = 256;
+        cached = cus;
+    }
+    return cached;
+}
+
+size_t dkv_partial_bytes(const wlb_attn_desc& d, const wlb_plan_layout& L) {
+    // one fp32 dK^T and dV^T tile per partial result
+    return (size_t)L.dkv_max_partials * (2 * (size_t)kBwdKeyTile * d.head_dim * sizeof(float));
+}
+
 void plan_layout(const wlb_attn_desc& d, wlb_plan_layout* L) {
     L->group_rows = kGroupRows;
     L->n_groups = (d.n_q + kGroupRows - 1) / kGroupRows;
@@ -53,6 +70,13 @@ void plan_layout(const wlb_attn_desc& d, wlb_plan_layout* L) {
     L->off_key_range = take(sizeof(int32_t) * 2 * L->n_key_tiles);
     size_t key_cost = take(sizeof(int32_t) * L->n_key_tiles);   // scratch for the ordering
     (void)key_cost;
+    // Items per tile are the smallest power of two that brings an item under 1/kDkvSplit of a compute
+    // unit's mean load, so split tiles contribute fewer than 2 * kDkvSplit * CUs items in total.
+    L->dkv_max_partials = 2 * kDkvSplit * compute_units();
+    L->dkv_max_items = L->n_key_tiles * d.hkv + L->dkv_max_partials;
+    L->off_key_ways = take(sizeof(int32_t) * L->n_key_tiles);
+    L->off_key_item_base = take(sizeof(int32_t) * (L->n_key_tiles + 1));
+    L->off_key_slot_base = take(sizeof(int32_t) * (L->n_key_tiles + 1));
     L->plan_bytes = off;
 }
 
@@ -169,6 +193,70 @@ __global__ void plan_order_kernel(const int32_t* __restrict__ cost, int n, int32
     order[rank] = i;
 }
 
+// One workgroup.  Chooses how many items each key tile is split into and replaces the tile's
+// cost by its item cost (groups in range x heads per item), the key the tiles are then ordered by.
+__global__ void __launch_bounds__(1024) plan_key_split_kernel(const int32_t* __restrict__ key_range, int n_key_tiles,
+                                                              int hq, int hkv, int n_slots, int32_t* __restrict__ ways,
+                                                              int32_t* __restrict__ item_cost) {
+    __shared__ long long part[1024];
+    long long sum = 0;
+    for (int kt = threadIdx.x; kt < n_key_tiles; kt += 1024) sum += key_range[2 * kt + 1] - key_range[2 * kt];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int s = 512; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
+        __syncthreads();
+    }
+    const int G = hq / hkv;
+    const long long total_stages = part[0] * hq;
+    const long long thr = max(16LL, (total_stages + (long long)n_slots * kDkvSplit - 1) / ((long long)n_slots * kDkvSplit));
+    for (int kt = threadIdx.x; kt < n_key_tiles; kt += 1024) {
+        const int span = key_range[2 * kt + 1] - key_range[2 * kt];
+        int w = 1;
+#ifndef WLB_X_NOSPLIT
+        while (w < G && (long long)span * (G / w) > thr && G % (2 * w) == 0) w *= 2;
+#endif
+        ways[kt] = w;
+        item_cost[kt] = span * (G / w);
+    }
+}
+
+// One workgroup.  Exclusive prefix sums, by order rank, of the tiles' item counts and partial slots.
+__global__ void __launch_bounds__(1024) plan_key_bases_kernel(const int32_t* __restrict__ key_order,
+                                                              const int32_t* __restrict__ ways, int n_key_tiles, int hkv,
+                                                              int32_t* __restrict__ item_base, int32_t* __restrict__ slot_base) {
+    __shared__ int s_items[1024], s_slots[1024];
+    const int per = (n_key_tiles + 1023) / 1024;
+    const int r0 = threadIdx.x * per, r1 = min(r0 + per, n_key_tiles);
+    int items = 0, slots = 0;
+    for (int r = r0; r < r1; ++r) {
+        const int w = ways[key_order[r]];
+        items += w * hkv;
+        slots += w > 1 ? w * hkv : 0;
+    }
+    s_items[threadIdx.x] = items;
+    s_slots[threadIdx.x] = slots;
+    __syncthreads();
+    // Hillis-Steele inclusive scan over the 1024 per-thread totals
+    for (int o = 1; o < 1024; o <<= 1) {
+        const int a = (int)threadIdx.x >= o ? s_items[threadIdx.x - o] : 0;
+        const int b = (int)threadIdx.x >= o ? s_slots[threadIdx.x - o] : 0;
+        __syncthreads();
+        s_items[threadIdx.x] += a;
+        s_slots[threadIdx.x] += b;
+        __syncthreads();
+    }
+    int ib = s_items[threadIdx.x] - items, sb = s_slots[threadIdx.x] - slots;
+    for (int r = r0; r < r1; ++r) {
+        item_base[r] = ib;
+        slot_base[r] = sb;
+        const int w = ways[key_order[r]];
+        ib += w * hkv;
+        sb += w > 1 ? w * hkv : 0;
+    }
+    if (threadIdx.x == 1023) { item_base[n_key_tiles] = s_items[1023]; slot_base[n_key_tiles] = s_slots[1023]; }
+}
+
 wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const int32_t* q_idx,
                        const int32_t* cu_seqlens_k, char* ws, void* stream_) {
     hipStream_t stream = (hipStream_t)stream_;
@@ -188,7 +276,11 @@ wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const i
     plan_key_tiles_kernel<<<(L.n_key_tiles + 3) / 4, 256, 0, stream>>>(group, L.n_groups, L.n_key_tiles,
                                                                        kBwdKeyTile, d.t_kv, key_range, key_cost);
     plan_order_kernel<<<(L.n_fwd_tiles + 255) / 256, 256, 0, stream>>>(fwd_cost, L.n_fwd_tiles, fwd_order);
+    int32_t* key_ways = (int32_t*)(ws + L.off_key_ways);
+    plan_key_split_kernel<<<1, 1024, 0, stream>>>(key_range, L.n_key_tiles, d.hq, d.hkv, compute_units(), key_ways, key_cost);
     plan_order_kernel<<<(L.n_key_tiles + 255) / 256, 256, 0, stream>>>(key_cost, L.n_key_tiles, key_order);
+    plan_key_bases_kernel<<<1, 1024, 0, stream>>>(key_order, key_ways, L.n_key_tiles, d.hkv,
+                                                  (int32_t*)(ws + L.off_key_item_base), (int32_t*)(ws + L.off_key_slot_base));
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(WLB_ERR_HIP, "plan launch: %s", hipGetErrorString(e));
     return WLB_OK;
@@ -207,7 +299,7 @@ extern "C" wlb_status wlb_attn_workspace_size(const wlb_attn_desc* desc, size_t*
     wlb_plan_layout L;
     plan_layout(*desc, &L);
     *fwd_bytes = L.plan_bytes;
-    *bwd_bytes = L.plan_bytes + delta_bytes(*desc);
+    *bwd_bytes = L.plan_bytes + delta_bytes(*desc) + dkv_partial_bytes(*desc, L);
     return WLB_OK;
 }
 
@@ -256,7 +348,7 @@ extern "C" wlb_status wlb_attn_bwd(const wlb_attn_desc* desc, const void* q, con
     if (!reuse && (!q_idx || !cu_seqlens_k)) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_bwd: null q_idx/cu_seqlens_k");
     wlb_plan_layout L;
     plan_layout(*desc, &L);
-    const size_t need = L.plan_bytes + delta_bytes(*desc);
+    const size_t need = L.plan_bytes + delta_bytes(*desc) + dkv_partial_bytes(*desc, L);
     if (workspace_bytes < need)
         return fail(WLB_ERR_BUFFER_TOO_SMALL, "wlb_attn_bwd: workspace %zu < %zu bytes", workspace_bytes, need);
     if (!reuse)
