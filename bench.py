@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--config", type=int, default=2, help="workload index (2 = the 128K CP=8 config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-seq", action="store_true", help="skip the per-sequence sharding comparison")
+    ap.add_argument("--tiny-tail", action="store_true",
+                    help="measure the small-document (HBM-bound) regime instead: the 1..64-token documents of "
+                         "config 4 as their own 32768-token sequence, CP=1 and CP=4, reported as GB/s")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
@@ -67,8 +70,72 @@ class RankState:
         self.dv = torch.empty_like(full["v"])
 
 
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, published
+
+
+def tiny_tail(args):
+    """The small-document regime: HBM GB/s against the algorithmic byte count (Q, O, dO, dQ, LSE, delta per local
+    row; K, V read by forward and backward and dK, dV written for every token, per rank)."""
+    import torch
+    from paper_2503_17924_amd import binding as B
+    from paper_2503_17924_amd import workloads as wl
+    B.lib()
+    device = torch.device("cuda:0")
+    w = wl.config(4)
+    docs = w.doc_len[1:]                              # the 1..64-token documents that follow the long one
+    T = int(docs.sum())
+    hq, hkv, D = w.hq, w.hkv, w.head_dim
+    g = torch.Generator(device="cuda").manual_seed(1004)
+    mk = lambda n, h: torch.randn((n, h, D), device=device, generator=g, dtype=torch.float32).to(torch.bfloat16)
+    full = {"q": mk(T, hq), "k": mk(T, hkv), "v": mk(T, hkv), "do": mk(T, hq)}
+    out = {}
+    for cp in (1, 4):
+        states, nbytes = [], 0.0
+        for r in range(cp):
+            sh = B.wlb_shard(docs, cp, r, B.SHARD_PER_DOC_PADDED)
+            qi = sh["q_idx"]
+            rows = torch.from_numpy(np.maximum(qi, 0).astype(np.int64)).to(device)
+            st = {"attn": B.Attention(qi, sh["cu_seqlens_k"], T, hq, hkv, D, w.scale, device),
+                  "q": full["q"].index_select(0, rows).contiguous(), "do": full["do"].index_select(0, rows).contiguous()}
+            st["o"] = torch.empty_like(st["q"]); st["dq"] = torch.empty_like(st["q"])
+            st["lse"] = torch.empty((hq, len(qi)), dtype=torch.float32, device=device)
+            st["dk"] = torch.empty_like(full["k"]); st["dv"] = torch.empty_like(full["v"])
+            states.append(st)
+            n_real = int((qi >= 0).sum())
+            per_row = 2 * hq * D * 2 + 4 * hq            # forward: Q, O, LSE
+            per_row += 4 * hq * D * 2 + 4 * hq + 2 * 4 * hq   # backward: Q, O, dO read, dQ written, LSE read, delta written and read
+            per_tok = 2 * hkv * D * 2 + 2 * hkv * D * 2 + 2 * hkv * D * 2   # K, V read twice, dK, dV written
+            nbytes += n_real * per_row + T * per_tok
+
+        def run():
+            for st in states:
+                st["attn"].plan()
+                st["attn"].forward(st["q"], full["k"], full["v"], st["o"], st["lse"])
+                st["attn"].backward(st["q"], full["k"], full["v"], st["o"], st["lse"], st["do"], st["dq"], st["dk"], st["dv"])
+        for _ in range(max(args.warmup, 2)):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        out[f"cp{cp}"] = {"ms": round(ms, 4), "algorithmic_bytes": int(nbytes), "gb_per_s": round(nbytes / (ms * 1e-3) / 1e9, 1)}
+    best = out["cp1"]
+    print(json.dumps({
+        "metric": "HBM GB/s, small-document regime (schedule + attention fwd + bwd)", "value": best["gb_per_s"], "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": max(args.warmup, 2), "ms_per_step": best["ms"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c4_tiny_document_tail", "tokens": T, "n_docs": int(len(docs)), "hq": hq, "hkv": hkv, "head_dim": D},
+        "roofline": {"bound": "hbm", "achieved": best["gb_per_s"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(best["gb_per_s"] / PEAK_HBM_GBS, 4), "traffic": None},
+        "by_cp": out}))
+
+
 def main():
     args = parse()
+    if args.tiny_tail:
+        return tiny_tail(args)
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU (context-parallel ranks are emulated in turn); "
               f"--gpus {args.gpus} is not supported", file=sys.stderr)

@@ -18,7 +18,10 @@ constexpr int kBwdKeyTile = 128;  // keys per dK/dV work item
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 constexpr int kLists = 8;         // XCDs: workgroup b runs on XCD b % 8
-constexpr int kDkvSplit = 8;      // a dK/dV item is at most 1/kDkvSplit of the mean load of a compute unit
+#ifndef WLB_DKV_SPLIT
+#define WLB_DKV_SPLIT 8
+#endif
+constexpr int kDkvSplit = WLB_DKV_SPLIT;      // a dK/dV item is at most 1/kDkvSplit of the mean load of a compute unit
 
 // compute units of the GPU (256 when none is present: layout queries on the host)
 int compute_units();

@@ -129,10 +129,25 @@ def test_schedule_tables():
                 assert krange[kt, 0] == sees[0] and krange[kt, 1] == sees[-1] + 1
             else:
                 assert krange[kt, 0] == krange[kt, 1]
-        kcount = [krange[kt, 1] - krange[kt, 0] for kt in korder]
-        # heaviest-first: the count of groups that touch a tile never increases by more than
-        # the skipped (non-touching) groups inside the range; with sorted rows there are none
-        assert kcount[0] == max(kcount)
+        # dK/dV items: a tile is cut by heads into a power-of-two number of items, tiles are ordered by
+        # item cost (groups in range x heads per item), heaviest first, and the item / partial-slot
+        # bases are the running sums in that order
+        ways = arr(lay.off_key_ways, lay.n_key_tiles)
+        item_base = arr(lay.off_key_item_base, lay.n_key_tiles + 1)
+        slot_base = arr(lay.off_key_slot_base, lay.n_key_tiles + 1)
+        g_heads = c.hq // c.hkv
+        assert all(w in (1, 2, 4, 8) and g_heads % w == 0 for w in ways.tolist())
+        span = krange[:, 1] - krange[:, 0]
+        icost = span * (g_heads // ways)
+        assert (np.diff(icost[korder]) <= 0).all()
+        assert item_base[0] == 0 and slot_base[0] == 0
+        assert (np.diff(item_base) == ways[korder] * c.hkv).all()
+        assert (np.diff(slot_base) == np.where(ways[korder] > 1, ways[korder] * c.hkv, 0)).all()
+        assert item_base[-1] <= lay.dkv_max_items and slot_base[-1] <= lay.dkv_max_partials
+        # no item is heavier than the threshold unless it is already a single head
+        total = int(span.sum()) * c.hq
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        assert (icost[ways < g_heads] <= max(16, -(-total // (8 * n_cu)))).all()
 
 
 BWD_CASES = [
