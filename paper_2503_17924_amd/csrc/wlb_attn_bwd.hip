@@ -444,32 +444,38 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
 #pragma unroll
                         for (int qb = 0; qb < 2; ++qb) s2[qb] = mfma32(qa[qb][ks], bop[kh * (KS / 2) + ks], s2[qb]);
                 }
+                // exponentials, mask, bf16; one uniform branch around the whole block (the mask is
+                // needed only on a document's diagonal or edge), so the common path is straight-line
+                auto probs = [&](auto masked_tag) __attribute__((always_inline)) {
+                    constexpr bool masked = decltype(masked_tag)::value;
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb) {
-                    const f32x16 s = s2[qb];
-                    float pr[16];
+                    for (int qb = 0; qb < 2; ++qb) {
+                        const f32x16 s = s2[qb];
+                        float pr[16];
 #pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        const int qrow = qb * 32 + r4 * 8 + half * 4;
-                        const f32x4 ls = *reinterpret_cast<const f32x4*>(&lse_s[buf][qrow]);
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            const int qrow = qb * 32 + r4 * 8 + half * 4;
+                            const f32x4 ls = *reinterpret_cast<const f32x4*>(&lse_s[buf][qrow]);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) pr[r4 * 4 + i] = fast_exp2(fmaf(s[r4 * 4 + i], cs, -ls[i]));
-                        if (!full) {
-                            asm volatile("");   // keep the mask a branch
-                            const i32x4 l4 = *reinterpret_cast<const i32x4*>(&lo_s[buf][qrow]);
-                            const i32x4 h4 = *reinterpret_cast<const i32x4*>(&hi_s[buf][qrow]);
+                            for (int i = 0; i < 4; ++i) pr[r4 * 4 + i] = fast_exp2(fmaf(s[r4 * 4 + i], cs, -ls[i]));
+                            if (masked) {
+                                const i32x4 l4 = *reinterpret_cast<const i32x4*>(&lo_s[buf][qrow]);
+                                const i32x4 h4 = *reinterpret_cast<const i32x4*>(&hi_s[buf][qrow]);
 #pragma unroll
-                            for (int i = 0; i < 4; ++i)
-                                pr[r4 * 4 + i] = (mykey >= l4[i] && mykey < h4[i]) ? pr[r4 * 4 + i] : 0.f;
+                                for (int i = 0; i < 4; ++i)
+                                    pr[r4 * 4 + i] = (mykey >= l4[i] && mykey < h4[i]) ? pr[r4 * 4 + i] : 0.f;
+                            }
+                        }
+#pragma unroll
+                        for (int cc = 0; cc < 2; ++cc) {
+                            pf[qb][cc] = pack8(pr[8 * cc + 0], pr[8 * cc + 1], pr[8 * cc + 2], pr[8 * cc + 3],
+                                               pr[8 * cc + 4], pr[8 * cc + 5], pr[8 * cc + 6], pr[8 * cc + 7]);
+                            *reinterpret_cast<WLB_LDS bf16x8*>((uintptr_t)(pbuf_lane + (qb * 2 + cc) * 1024)) = pf[qb][cc];
                         }
                     }
-#pragma unroll
-                    for (int cc = 0; cc < 2; ++cc) {
-                        pf[qb][cc] = pack8(pr[8 * cc + 0], pr[8 * cc + 1], pr[8 * cc + 2], pr[8 * cc + 3],
-                                           pr[8 * cc + 4], pr[8 * cc + 5], pr[8 * cc + 6], pr[8 * cc + 7]);
-                        *reinterpret_cast<WLB_LDS bf16x8*>((uintptr_t)(pbuf_lane + (qb * 2 + cc) * 1024)) = pf[qb][cc];
-                    }
-                }
+                };
+                if (full) probs(std::false_type{});
+                else probs(std::true_type{});
             } else {
 #pragma unroll
                 for (int qb = 0; qb < 2; ++qb)
@@ -672,7 +678,11 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     if (d.head_dim == 128) { if (do_delta) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p); }
     else { if (do_delta) delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p); }
     hipStream_t dq_stream = stream;
+#ifdef WLB_X_NOSIDE
+    SideStream* side = nullptr;
+#else
     SideStream* side = (do_dq && do_dkv) ? side_stream() : nullptr;
+#endif
     if (side) {
         if (hipEventRecord(side->fork, stream) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
             return fail(WLB_ERR_HIP, "backward: fork to the second stream failed");
