@@ -190,7 +190,12 @@ enum {
      * kernel (dq is left untouched); do not run the dK/dV kernel (dk, dv left untouched). */
     WLB_ATTN_BWD_SKIP_DELTA = 2,
     WLB_ATTN_BWD_SKIP_DQ = 4,
-    WLB_ATTN_BWD_SKIP_DKV = 8
+    WLB_ATTN_BWD_SKIP_DKV = 8,
+    /* By default wlb_attn_bwd runs its dQ kernel on a second stream owned by the library (forked
+     * from and joined to the caller's stream with events), so that the dQ and dK/dV kernels fill
+     * each other's idle compute units.  With this flag everything runs on the caller's stream, one
+     * kernel after the other: each kernel's duration is then its own (profiling). */
+    WLB_ATTN_BWD_NO_OVERLAP = 16
 };
 
 /* Bytes of device workspace needed (256-byte aligned pointer expected).  The forward needs

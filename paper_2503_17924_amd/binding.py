@@ -25,6 +25,7 @@ ATTN_REUSE_PLAN = 1
 ATTN_BWD_SKIP_DELTA = 2
 ATTN_BWD_SKIP_DQ = 4
 ATTN_BWD_SKIP_DKV = 8
+ATTN_BWD_NO_OVERLAP = 16
 
 STATUS_NAMES = {0: "WLB_OK", 1: "WLB_ERR_INVALID_ARG", 2: "WLB_ERR_BUFFER_TOO_SMALL",
                 3: "WLB_ERR_UNSUPPORTED", 4: "WLB_ERR_HIP"}

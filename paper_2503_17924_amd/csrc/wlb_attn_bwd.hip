@@ -678,11 +678,7 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     if (d.head_dim == 128) { if (do_delta) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p); }
     else { if (do_delta) delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p); }
     hipStream_t dq_stream = stream;
-#ifdef WLB_X_NOSIDE
-    SideStream* side = nullptr;
-#else
-    SideStream* side = (do_dq && do_dkv) ? side_stream() : nullptr;
-#endif
+    SideStream* side = (do_dq && do_dkv && !(d.flags & WLB_ATTN_BWD_NO_OVERLAP)) ? side_stream() : nullptr;
     if (side) {
         if (hipEventRecord(side->fork, stream) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
             return fail(WLB_ERR_HIP, "backward: fork to the second stream failed");
