@@ -217,7 +217,11 @@ __global__ void __launch_bounds__(1024) plan_key_split_kernel(const int32_t* __r
         while (w < G && (long long)span * (G / w) > thr && G % (2 * w) == 0) w *= 2;
 #endif
         ways[kt] = w;
+#ifdef WLB_X_SPANORDER
+        item_cost[kt] = span;
+#else
         item_cost[kt] = span * (G / w);
+#endif
     }
 }
 
