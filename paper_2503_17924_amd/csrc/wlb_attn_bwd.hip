@@ -6,13 +6,15 @@
 // dK/dV summed over the query heads that share a KV head.  As in all-gather context
 // parallelism (Section 2.1) dK/dV hold only the calling rank's rows' contribution.
 //
-// Three kernels, no atomics, deterministic:
-//   delta_kernel  delta[h][i] = sum_d dO*O and the log2-scaled LSE copy (0 / +inf for padding rows)
-//   dq_kernel     query-stationary, same tiling as the forward: S^T and dP^T per lane column,
-//                 dQ^T += K^T dS^T with K^T read from LDS by transpose reads
-//   dkv_kernel    key-stationary: a workgroup owns 128 keys of one KV head and streams the row
-//                 groups that can see them through LDS for every query head of the KV group;
-//                 dK^T, dV^T stay in registers until the single final store.
+// Four kernels, no atomics, deterministic:
+//   delta_kernel      delta[h][i] = sum_d dO*O and the log2-scaled LSE copy (0 / +inf for padding rows)
+//   dq_kernel         query-stationary, same tiling as the forward: S^T and dP^T per lane column,
+//                     dQ^T += K^T dS^T with K^T read from LDS by transpose reads
+//   dkv_kernel        key-stationary: a work item owns 128 keys of one KV head and streams the row
+//                     groups that can see them through LDS for some or all query heads of the KV
+//                     group; dK^T, dV^T stay in registers until the single final store
+//   dkv_fixup_kernel  sums the fp32 partial results of key tiles whose heads were divided among
+//                     several work items (heavy tiles, so that no item is a straggler)
 // S and dP are recomputed in both dq_kernel and dkv_kernel (7 GEMMs for the 5 the derivative
 // needs): this keeps dQ free of atomics and of an fp32 accumulation buffer.
 // Q / dO / K tiles that are read both row-wise (b128) and column-wise (transpose reads) are
@@ -252,8 +254,11 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
 // more than 256 registers, i.e. one wavefront per SIMD, which measured slower here: splitting
 // halves the register need, so two wavefronts share a SIMD and hide each other's LDS and
 // barrier latencies, at the price of a second barrier per stage and 4 KiB of P traffic.
-// Stages (row group, query head) stream through LDS exactly as in dkv_kernel; per stage:
+// Stages (row group, query head) stream through LDS, double buffered; per stage:
 //   barrier 1 (tiles landed) -> phase 1 (S,P | dP) -> barrier 2 (P visible) -> phase 2 (dV | dS,dK).
+// A work item is a key tile with all query heads of one KV head, or - for a tile whose work
+// exceeds a threshold set by the schedule - a 1/2, 1/4 or 1/8 of those heads; such an item
+// writes its dK^T / dV^T as an unscaled fp32 partial result instead of the final bf16 rows.
 template <int D>
 __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
     constexpr int BNK = kBwdKeyTile, GR = kGroupRows, KS = D / 16, DB = D / 32, CPR = D / 8;
