@@ -252,25 +252,25 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
 // keys: they compute dP = dO V^T, take P from the partner, form dS = P o (dP - delta) and
 // accumulate dK^T += Q^T dS.  A wavefront that held K, V, dK^T and dV^T together would need
 // more than 256 registers, i.e. one wavefront per SIMD, which measured slower here: splitting
-// halves the register need, so two wavefronts share a SIMD and hide each other's LDS and
-// barrier latencies, at the price of a second barrier per stage and 4 KiB of P traffic.
-// Stages (row group, query head) stream through LDS, double buffered; per stage:
-//   barrier 1 (tiles landed) -> phase 1 (S,P | dP) -> barrier 2 (P visible) -> phase 2 (dV | dS,dK).
+// halves the register need, so two wavefronts share a SIMD and hide each other's LDS latencies.
+// Stages (row group, query head) stream through three LDS buffers.  The gradient role works one
+// stage behind the score role: between two workgroup barriers the score wavefronts run stage t
+// (S, P, dV) while the gradient wavefronts run stage t-1 (dP, dS, dK) with the P that was
+// written before the barrier.  One barrier per stage, and both roles carry the same load
+// (32 MFMAs plus the exponentials resp. the dS products), so neither waits for the other.
 // A work item is a key tile with all query heads of one KV head, or - for a tile whose work
 // exceeds a threshold set by the schedule - a 1/2, 1/4 or 1/8 of those heads; such an item
 // writes its dK^T / dV^T as an unscaled fp32 partial result instead of the final bf16 rows.
 template <int D>
 __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
     constexpr int BNK = kBwdKeyTile, GR = kGroupRows, KS = D / 16, DB = D / 32, CPR = D / 8;
-    constexpr int ROWB = D * 2, TILEB = GR * ROWB, NW = 8;
+    constexpr int ROWB = D * 2, TILEB = GR * ROWB, NW = 8, NBUF = 3, PBYTES = 4 * 2 * 2 * 1024;
     static_assert(BNK == 128 && GR == 64, "tiling");
 
-    __shared__ __attribute__((aligned(1024))) char smem[4 * TILEB];          // Q0 | Q1 | dO0 | dO1, swizzled
-    __shared__ __attribute__((aligned(1024))) char pbuf[4 * 2 * 2 * 1024];   // P: [key block][row block][half of 16 rows][lane] x 16 B
-    __shared__ __attribute__((aligned(16))) float lse_s[2][GR];
-    __shared__ __attribute__((aligned(16))) float dl_s[2][GR];
-    __shared__ __attribute__((aligned(16))) int lo_s[2][GR];
-    __shared__ __attribute__((aligned(16))) int hi_s[2][GR];
+    __shared__ __attribute__((aligned(1024))) char smem[NBUF * 2 * TILEB];   // per stage buffer: Q tile | dO tile, swizzled
+    // P of two stages (aligned so that one XOR switches stage): [key block][row block][half of 16 rows][lane] x 16 B
+    __shared__ __attribute__((aligned(2 * PBYTES))) char pbuf[2 * PBYTES];
+    __shared__ __attribute__((aligned(256))) int small_s[NBUF][4][GR];       // per stage buffer: lse2 | delta | row_lo | row_hi
 
     const int G = p.hq / p.hkv;
     // Work item blockIdx.x: tiles in order (heaviest item first), a tile's items consecutive:
@@ -299,19 +299,21 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
     const int l32 = lane & 31, half = lane >> 5;
     const int j16 = lane & 15, gi = (lane >> 4) & 1;
     const float cs = p.scale_log2e;
+    const int k0 = kt * BNK;
+    const int kw0 = k0 + kblk * 32;
+    const int mykey = kw0 + l32;
 
     const uint32_t q_row = (uint32_t)p.hq * D;
     const uint32_t q_total = (uint32_t)p.n_q * q_row * 2u;
     TileDma<D, GR, NW> dma;
     dma.init(wave, lane, q_row);
     const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
-    auto tile_ptr = [&](int which) { return smem_base + (uint32_t)(which * TILEB); };
-    auto issue_stage = [&](int g, int h, int buf) {
+    auto issue_stage = [&](int g, int h, int b) {
         BufRsrc qrs, ors;
         qrs.init(p.q + (size_t)h * D, q_total - (uint32_t)h * ROWB);
         ors.init(p.d_o + (size_t)h * D, q_total - (uint32_t)h * ROWB);
-        dma.issue(qrs, tile_ptr(buf), g * GR, wave);
-        dma.issue(ors, tile_ptr(2 + buf), g * GR, wave);
+        dma.issue(qrs, smem_base + (uint32_t)((2 * b) * TILEB), g * GR, wave);
+        dma.issue(ors, smem_base + (uint32_t)((2 * b + 1) * TILEB), g * GR, wave);
     };
     // Per-row scalars of a stage (visible key interval, log2-scaled LSE, delta) are copied
     // global->LDS asynchronously as well, by wavefront 0: no register load sits between the copies
@@ -333,34 +335,53 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
             auto lds_of = [&](const void* ptr) __attribute__((always_inline)) {
                 return (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)(WLB_LDS const void*)ptr);
             };
-            dma_issue_256(lo_rs.r, lds_of(&lo_s[b][0]), lane * 4, soff);
-            dma_issue_256(hi_rs.r, lds_of(&hi_s[b][0]), lane * 4, soff);
-            dma_issue_256(ls_rs.r, lds_of(&lse_s[b][0]), lane * 4, soff);
-            dma_issue_256(dl_rs.r, lds_of(&dl_s[b][0]), lane * 4, soff);
+            dma_issue_256(ls_rs.r, lds_of(&small_s[b][0][0]), lane * 4, soff);
+            dma_issue_256(dl_rs.r, lds_of(&small_s[b][1][0]), lane * 4, soff);
+            dma_issue_256(lo_rs.r, lds_of(&small_s[b][2][0]), lane * 4, soff);
+            dma_issue_256(hi_rs.r, lds_of(&small_s[b][3][0]), lane * 4, soff);
         }
     };
 
-    int naddr[KS], taddr[DB][2];
+    // LDS addresses, absolute and per role, rotated through the three stage buffers by one add per
+    // stage so that every access in the regions is register + immediate:
+    //   naddr: rows of the tile read row-wise      (score role: Q of its stage, gradient role: dO of its stage)
+    //   taddr: rows of the tile read transposed    (score role: dO,             gradient role: Q)
+    //   saddr: this lane's 4 rows of the per-row scalars;  paddr: this lane's slot of the P buffer
+    // The score role starts at buffer 0 (stage 0); the gradient role works one stage behind and
+    // starts at the last buffer.
+    const int rot0 = role == 0 ? 0 : NBUF - 1;
+    const uint32_t stage_base = smem_base + (uint32_t)rot0 * (2 * TILEB);
+    uint32_t naddr[KS], taddr[DB];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) naddr[ks] = l32 * ROWB + swz<CPR>(l32, ks * 2 + half) * 16;
+    for (int ks = 0; ks < KS; ++ks)
+        naddr[ks] = stage_base + (role == 0 ? 0 : TILEB) + l32 * ROWB + swz<CPR>(l32, ks * 2 + half) * 16;
+    // transposed reads: rows qq and qq+8 of a 16-row step; the swizzle of row qq+8 is that of row
+    // qq with bit 1 flipped, and tiles are 1 KiB aligned, so the second address is the first
+    // with address bit 5 flipped plus 8 rows
+    static_assert(swz<CPR>(8, 0) == (swz<CPR>(0, 0) ^ 2) && swz<CPR>(13, 5) == (swz<CPR>(5, 5) ^ 2), "row+8 flips swizzle bit 1");
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int db = 0; db < DB; ++db) {
+        const int qq = half * 4 + (j16 >> 2);
+        const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
+        taddr[db] = stage_base + (role == 0 ? TILEB : 0) + qq * ROWB + swz<CPR>(qq, dch) * 16 + (j16 & 1) * 8;
+    }
+    uint32_t saddr = (uint32_t)(uintptr_t)(WLB_LDS char*)&small_s[0][0][0] + (uint32_t)rot0 * (4 * GR * 4) + half * 16;
+    // score role: P buffer of its stage, gradient role: of the stage before
+    uint32_t paddr = ((uint32_t)(uintptr_t)(WLB_LDS char*)pbuf + kblk * 4096 + lane * 16) ^ (role == 0 ? 0u : (uint32_t)PBYTES);
+    // b = buffer of the stage the score role just ran
+    auto rotate = [&](int b) __attribute__((always_inline)) {
+        const bool wrap = role == 0 ? b == NBUF - 1 : b == 0;
+        const int dt = wrap ? -(NBUF - 1) * 2 * TILEB : 2 * TILEB;
+        const int dsm = wrap ? -(NBUF - 1) * 4 * GR * 4 : 4 * GR * 4;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int qq = t * 8 + half * 4 + (j16 >> 2);
-            const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
-            taddr[db][t] = qq * ROWB + swz<CPR>(qq, dch) * 16 + (j16 & 1) * 8;
-        }
-    const uint32_t pbuf_lane = (uint32_t)(uintptr_t)(WLB_LDS char*)pbuf + kblk * 4096 + lane * 16;
-
-    // stage t of the item is row group g_first + t / nh with query head h_first + t % nh; every
-    // group of the tile's range is a stage (one whose hull misses the tile, rare, costs a copy and no math)
-    const int g_first = ld_const(p.key_range + 2 * kt);
-    const int t1 = (ld_const(p.key_range + 2 * kt + 1) - g_first) * nh;
-    int buf = 0;
-    const int k0 = kt * BNK;
-    const int kw0 = k0 + kblk * 32;
-    const int mykey = kw0 + l32;
+        for (int ks = 0; ks < KS; ++ks) naddr[ks] += dt;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) taddr[db] += dt;
+        saddr += dsm;
+        paddr ^= (uint32_t)PBYTES;
+    };
+    auto lds_f4 = [&](uint32_t a) __attribute__((always_inline)) { return *reinterpret_cast<const WLB_LDS f32x4*>((uintptr_t)a); };
+    auto lds_i4 = [&](uint32_t a) __attribute__((always_inline)) { return *reinterpret_cast<const WLB_LDS i32x4*>((uintptr_t)a); };
 
     // this wavefront's B operands: K rows (score role) or V rows (gradient role) of its 32 keys
     bf16x8 bop[KS];
@@ -376,10 +397,139 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
+    // ---- pieces of a role's work on one stage
+    // A stage is eight units of four (D/32) MFMAs; the operands of unit u+1 are requested from LDS
+    // before the MFMAs of unit u are issued (two operand register sets), so that a wavefront by
+    // itself can keep MFMAs flowing and only the first unit of a stage waits for an LDS round trip.
+    struct RowOps { bf16x8 a[KS / 2]; };       // half the head dimension of 32 rows, read row-wise
+    struct ColOps { bf16x4 t[DB][2]; };        // 16 rows, read transposed
+    auto load_rows = [&](RowOps& o, int qb, int kh) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ks = 0; ks < KS / 2; ++ks)
+            o.a[ks] = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(naddr[kh * (KS / 2) + ks] + qb * 32 * ROWB));
+    };
+    auto load_cols = [&](ColOps& o, int st) __attribute__((always_inline)) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) o.t[db][t] = lds_read_tr4_at((t ? taddr[db] ^ 32u : taddr[db]) + (st * 16 + t * 8) * ROWB);
+    };
+    // S or dP of a 32-row block, half the head dimension: B operand = K or V
+    auto mfma_rows = [&](f32x16& sc, const RowOps& o, int kh) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ks = 0; ks < KS / 2; ++ks) sc = mfma32(o.a[ks], bop[kh * (KS / 2) + ks], sc);
+    };
+    // 16 rows: acc += tile^T x b  (score role: dV from dO^T, gradient role: dK from Q^T)
+    auto mfma_cols = [&](const ColOps& o, const bf16x8& b) __attribute__((always_inline)) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) acc[db] = mfma32(cat4(o.t[db][0], o.t[db][1]), b, acc[db]);
+    };
+    // Per-row scalars of 16 rows (8-row groups 2cc, 2cc+1 of row block qb; this lane's 4 rows of each):
+    // requested one unit ahead like the MFMA operands
+    struct RowVals { f32x4 v[2]; };
+    auto load_vals = [&](RowVals& o, int which, int qb, int cc) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r2 = 0; r2 < 2; ++r2) o.v[r2] = lds_f4(saddr + which * GR * 4 + (qb * 32 + (cc * 2 + r2) * 8) * 4);
+    };
+    // P of those 16 rows: exponentials, mask, bf16; returned as this wavefront's B operand and
+    // handed to the partner through LDS.  The mask is needed only on a document's diagonal or edge
+    // (uniform branch).
+    auto probs_half = [&](const f32x16& sc, const RowVals& ls, int qb, int cc, bool masked) __attribute__((always_inline)) {
+        float pr[8];
+#pragma unroll
+        for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pr[r2 * 4 + i] = fast_exp2(fmaf(sc[(cc * 2 + r2) * 4 + i], cs, -ls.v[r2][i]));
+        if (masked) {
+#pragma unroll
+            for (int r2 = 0; r2 < 2; ++r2) {
+                const int roff = (qb * 32 + (cc * 2 + r2) * 8) * 4;
+                const i32x4 l4 = lds_i4(saddr + 2 * GR * 4 + roff);
+                const i32x4 h4 = lds_i4(saddr + 3 * GR * 4 + roff);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    pr[r2 * 4 + i] = (mykey >= l4[i] && mykey < h4[i]) ? pr[r2 * 4 + i] : 0.f;
+            }
+        }
+        const bf16x8 pk = pack8(pr[0], pr[1], pr[2], pr[3], pr[4], pr[5], pr[6], pr[7]);
+        *reinterpret_cast<WLB_LDS bf16x8*>((uintptr_t)(paddr + (qb * 2 + cc) * 1024)) = pk;
+        return pk;
+    };
+    // dS of 16 rows: P (from the partner) x (dP - delta)
+    auto load_p = [&](int qb, int cc) __attribute__((always_inline)) {
+        return *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(paddr + (qb * 2 + cc) * 1024));
+    };
+    auto ds_half = [&](const f32x16& dn, const bf16x8& pv, const RowVals& dl, int cc) __attribute__((always_inline)) {
+        float ds[8];
+#pragma unroll
+        for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ds[r2 * 4 + i] = (float)pv[r2 * 4 + i] * (dn[(cc * 2 + r2) * 4 + i] - dl.v[r2][i]);
+        return pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
+    };
+    // The fences pin the order "request unit u+1, run unit u"; the exponentials / dS products of
+    // one row block are placed beside the MFMAs of the units that do not depend on them.
+    auto fence = [] () __attribute__((always_inline)) { __builtin_amdgcn_sched_barrier(0); };
+    auto score_stage = [&](bool masked) __attribute__((always_inline)) {
+        f32x16 s0, s1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+        RowOps ra, rb;
+        ColOps ca, cb;
+        RowVals la, lb;
+        load_rows(ra, 0, 0);
+        load_rows(rb, 0, 1);                          fence();  mfma_rows(s0, ra, 0);  fence();
+        load_rows(ra, 1, 0);  load_vals(la, 0, 0, 0); fence();  mfma_rows(s0, rb, 1);  fence();
+        load_rows(rb, 1, 1);  load_vals(lb, 0, 0, 1); fence();  mfma_rows(s1, ra, 0);
+        const bf16x8 p00 = probs_half(s0, la, 0, 0, masked);
+        fence();
+        load_cols(ca, 0);     load_vals(la, 0, 1, 0); fence();  mfma_rows(s1, rb, 1);
+        const bf16x8 p01 = probs_half(s0, lb, 0, 1, masked);
+        fence();
+        load_cols(cb, 1);     load_vals(lb, 0, 1, 1); fence();  mfma_cols(ca, p00);
+        const bf16x8 p10 = probs_half(s1, la, 1, 0, masked);
+        fence();
+        load_cols(ca, 2);                             fence();  mfma_cols(cb, p01);
+        const bf16x8 p11 = probs_half(s1, lb, 1, 1, masked);
+        fence();
+        load_cols(cb, 3);                             fence();  mfma_cols(ca, p10);  fence();
+        mfma_cols(cb, p11);
+    };
+    auto grad_stage = [&]() __attribute__((always_inline)) {
+        f32x16 d0, d1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { d0[r] = 0.f; d1[r] = 0.f; }
+        RowOps ra, rb;
+        ColOps ca, cb;
+        RowVals la, lb;
+        bf16x8 pa, pb;
+        load_rows(ra, 0, 0);
+        load_rows(rb, 0, 1);                                               fence();  mfma_rows(d0, ra, 0);  fence();
+        load_rows(ra, 1, 0);  load_vals(la, 1, 0, 0);  pa = load_p(0, 0);  fence();  mfma_rows(d0, rb, 1);  fence();
+        load_rows(rb, 1, 1);  load_vals(lb, 1, 0, 1);  pb = load_p(0, 1);  fence();  mfma_rows(d1, ra, 0);
+        const bf16x8 e00 = ds_half(d0, pa, la, 0);
+        fence();
+        load_cols(ca, 0);     load_vals(la, 1, 1, 0);  pa = load_p(1, 0);  fence();  mfma_rows(d1, rb, 1);
+        const bf16x8 e01 = ds_half(d0, pb, lb, 1);
+        fence();
+        load_cols(cb, 1);     load_vals(lb, 1, 1, 1);  pb = load_p(1, 1);  fence();  mfma_cols(ca, e00);
+        const bf16x8 e10 = ds_half(d1, pa, la, 0);
+        fence();
+        load_cols(ca, 2);                                                  fence();  mfma_cols(cb, e01);
+        const bf16x8 e11 = ds_half(d1, pb, lb, 1);
+        fence();
+        load_cols(cb, 3);                                                  fence();  mfma_cols(ca, e10);  fence();
+        mfma_cols(cb, e11);
+    };
+
+    // stage t of the item is row group g_first + t / nh with query head h_first + t % nh; every
+    // group of the tile's range is a stage (one whose hull misses the tile, rare, costs a copy and no math)
+    const int g_first = ld_const(p.key_range + 2 * kt);
+    const int t1 = (ld_const(p.key_range + 2 * kt + 1) - g_first) * nh;
+
     // The schedule data of a stage (its group's hull, fully visible range and real-row count) comes
-    // by scalar loads issued one stage ahead, just before the mid-stage barrier, and is turned into
-    // the next stage's flags right after it: a load at the top of a stage would put its whole
-    // latency in front of the stage's first barrier.
+    // by scalar loads issued right after the barrier of the stage before and is turned into flags
+    // at that stage's end: a load at the top of a stage would put its latency in front of the barrier.
     struct Flags { bool full, live, pads; };
     auto flags_of = [&](const int4& gd, int real, int g) {
         Flags f;
@@ -388,188 +538,57 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
         f.pads = real < min(GR, p.n_q - g * GR);
         return f;
     };
-    int t = 0;
     Flags cur_f{false, false, false};
-    if (t < t1) {
+    if (t1 > 0) {
         cur_f = flags_of(ld_const4(p.group + 4 * g_first), ld_const(p.group_real + g_first), g_first);
-        issue_stage(g_first, h_first, buf);
-        load_small(g_first, h_first, buf);
+        issue_stage(g_first, h_first, 0);
+        load_small(g_first, h_first, 0);
     }
     // no compiler-visible vector load may be pending inside the stage loop (it would wait for the copies too)
     wait_vmem();
-    while (t < t1) {
-        const int g = g_first + t / nh;
-        const int tn = t + 1;
-        const int gn = g_first + tn / nh, hn = tn % nh;
-        const bool full = cur_f.full, wave_live = cur_f.live, has_pads = cur_f.pads;
+    int g = g_first, hh = 0, b = 0;      // the score role's stage t = (g, hh) in buffer b
+    bool live_prev = false;
+    for (int t = 0; t <= t1 && t1 > 0; ++t) {
+        const bool have = t < t1, have_next = t + 1 < t1;
+        const bool full = cur_f.full, live = have && cur_f.live, has_pads = have && cur_f.pads;
+        int gn = g, hn = hh + 1;
+        if (hn == nh) { hn = 0; gn = g + 1; }
+        const int bn = b == NBUF - 1 ? 0 : b + 1;
 
         wait_vmem();
-        __syncthreads();      // barrier 1: stage (g, hh) is in LDS; everyone has left the other buffers and pbuf
-        if (tn < t1) {
-            issue_stage(gn, h_first + hn, buf ^ 1);
-            load_small(gn, h_first + hn, buf ^ 1);
-        }
         if (has_pads) {
+            __syncthreads();      // stage t's tiles and row scalars are in LDS
             const int r = tid >> 3, part = tid & 7;       // 512 threads: 8 per row
-            if (hi_s[buf][r] == 0) {
+            if (small_s[b][3][r] == 0) {
                 const i32x4 z = {0, 0, 0, 0};
 #pragma unroll
                 for (int i = 0; i < CPR / 8; ++i) {
-                    *reinterpret_cast<i32x4*>(smem + buf * TILEB + r * ROWB + (part * (CPR / 8) + i) * 16) = z;
-                    *reinterpret_cast<i32x4*>(smem + (2 + buf) * TILEB + r * ROWB + (part * (CPR / 8) + i) * 16) = z;
+                    *reinterpret_cast<i32x4*>(smem + (2 * b) * TILEB + r * ROWB + (part * (CPR / 8) + i) * 16) = z;
+                    *reinterpret_cast<i32x4*>(smem + (2 * b + 1) * TILEB + r * ROWB + (part * (CPR / 8) + i) * 16) = z;
                 }
             }
-            __syncthreads();
         }
-        const uint32_t qb_base = smem_base + buf * TILEB, ob_base = smem_base + (2 + buf) * TILEB;
-
-        // ---------------- phase 1
-        bf16x8 pf[2][2];          // score role: P as MFMA B operands, [row block][16-row half]
-        f32x16 dp[2];             // gradient role: dP
-        if (wave_live) {
-            if (role == 0) {
-                // operands are requested half the head dimension at a time (8 reads in flight),
-                // the two row blocks' accumulation chains are interleaved
-                f32x16 s2[2];
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) s2[qb][r] = 0.f;
-#pragma unroll
-                for (int kh = 0; kh < 2; ++kh) {
-                    bf16x8 qa[2][KS / 2];
-#pragma unroll
-                    for (int ks = 0; ks < KS / 2; ++ks)
-#pragma unroll
-                        for (int qb = 0; qb < 2; ++qb)
-                            qa[qb][ks] = *reinterpret_cast<const WLB_LDS bf16x8*>(
-                                (uintptr_t)(qb_base + naddr[kh * (KS / 2) + ks] + qb * 32 * ROWB));
-#pragma unroll
-                    for (int ks = 0; ks < KS / 2; ++ks)
-#pragma unroll
-                        for (int qb = 0; qb < 2; ++qb) s2[qb] = mfma32(qa[qb][ks], bop[kh * (KS / 2) + ks], s2[qb]);
-                }
-                // exponentials, mask, bf16; one uniform branch around the whole block (the mask is
-                // needed only on a document's diagonal or edge), so the common path is straight-line
-                auto probs = [&](auto masked_tag) __attribute__((always_inline)) {
-                    constexpr bool masked = decltype(masked_tag)::value;
-#pragma unroll
-                    for (int qb = 0; qb < 2; ++qb) {
-                        const f32x16 s = s2[qb];
-                        float pr[16];
-#pragma unroll
-                        for (int r4 = 0; r4 < 4; ++r4) {
-                            const int qrow = qb * 32 + r4 * 8 + half * 4;
-                            const f32x4 ls = *reinterpret_cast<const f32x4*>(&lse_s[buf][qrow]);
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) pr[r4 * 4 + i] = fast_exp2(fmaf(s[r4 * 4 + i], cs, -ls[i]));
-                            if (masked) {
-                                const i32x4 l4 = *reinterpret_cast<const i32x4*>(&lo_s[buf][qrow]);
-                                const i32x4 h4 = *reinterpret_cast<const i32x4*>(&hi_s[buf][qrow]);
-#pragma unroll
-                                for (int i = 0; i < 4; ++i)
-                                    pr[r4 * 4 + i] = (mykey >= l4[i] && mykey < h4[i]) ? pr[r4 * 4 + i] : 0.f;
-                            }
-                        }
-#pragma unroll
-                        for (int cc = 0; cc < 2; ++cc) {
-                            pf[qb][cc] = pack8(pr[8 * cc + 0], pr[8 * cc + 1], pr[8 * cc + 2], pr[8 * cc + 3],
-                                               pr[8 * cc + 4], pr[8 * cc + 5], pr[8 * cc + 6], pr[8 * cc + 7]);
-                            *reinterpret_cast<WLB_LDS bf16x8*>((uintptr_t)(pbuf_lane + (qb * 2 + cc) * 1024)) = pf[qb][cc];
-                        }
-                    }
-                };
-                if (full) probs(std::false_type{});
-                else probs(std::true_type{});
-            } else {
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) dp[qb][r] = 0.f;
-#pragma unroll
-                for (int kh = 0; kh < 2; ++kh) {
-                    bf16x8 ga[2][KS / 2];
-#pragma unroll
-                    for (int ks = 0; ks < KS / 2; ++ks)
-#pragma unroll
-                        for (int qb = 0; qb < 2; ++qb)
-                            ga[qb][ks] = *reinterpret_cast<const WLB_LDS bf16x8*>(
-                                (uintptr_t)(ob_base + naddr[kh * (KS / 2) + ks] + qb * 32 * ROWB));
-#pragma unroll
-                    for (int ks = 0; ks < KS / 2; ++ks)
-#pragma unroll
-                        for (int qb = 0; qb < 2; ++qb) dp[qb] = mfma32(ga[qb][ks], bop[kh * (KS / 2) + ks], dp[qb]);
-                }
-            }
+        __syncthreads();          // stage t is in LDS, P of stage t-1 is visible, everyone has left
+                                  // the buffer of stage t-2 and the P buffer of stage t-2
+        if (have_next) {
+            issue_stage(gn, h_first + hn, bn);
+            load_small(gn, h_first + hn, bn);
         }
         int4 gd_n = int4{0, 0, 0, 0};
         int real_n = 0;
-        const bool new_group = tn < t1 && gn != g;
+        const bool new_group = have_next && gn != g;
         if (new_group) { gd_n = ld_const4(p.group + 4 * gn); real_n = ld_const(p.group_real + gn); }
-        __syncthreads();      // barrier 2: P of this stage is visible to the partners
-        if (new_group) cur_f = flags_of(gd_n, real_n, gn);
 
-        // ---------------- phase 2
-        if (wave_live) {
-            if (role == 0) {
-                // four steps of 16 rows; the transposed dO operands of step i+1 are requested
-                // before the MFMAs of step i are issued
-                bf16x4 tv[2][DB][2];
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) tv[0][db][t] = lds_read_tr4_at(ob_base + taddr[db][t]);
-#pragma unroll
-                for (int st = 0; st < 4; ++st) {
-                    if (st + 1 < 4) {
-#pragma unroll
-                        for (int db = 0; db < DB; ++db)
-#pragma unroll
-                            for (int t = 0; t < 2; ++t)
-                                tv[(st + 1) & 1][db][t] = lds_read_tr4_at(ob_base + taddr[db][t] + (st + 1) * 16 * ROWB);
-                    }
-#pragma unroll
-                    for (int db = 0; db < DB; ++db)
-                        acc[db] = mfma32(cat4(tv[st & 1][db][0], tv[st & 1][db][1]), pf[st >> 1][st & 1], acc[db]);
-                }
-            } else {
-                bf16x4 tv[2][DB][2];
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) tv[0][db][t] = lds_read_tr4_at(qb_base + taddr[db][t]);
-                bf16x8 dsf[4];
-#pragma unroll
-                for (int st = 0; st < 4; ++st) {
-                    const int qb = st >> 1, cc = st & 1;
-                    const bf16x8 pv = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(pbuf_lane + st * 1024));
-                    float ds[8];
-#pragma unroll
-                    for (int r2 = 0; r2 < 2; ++r2) {
-                        const int qrow = qb * 32 + (cc * 2 + r2) * 8 + half * 4;
-                        const f32x4 dl = *reinterpret_cast<const f32x4*>(&dl_s[buf][qrow]);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            ds[r2 * 4 + i] = (float)pv[r2 * 4 + i] * (dp[qb][cc * 8 + r2 * 4 + i] - dl[i]);
-                    }
-                    dsf[st] = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
-                }
-#pragma unroll
-                for (int st = 0; st < 4; ++st) {
-                    if (st + 1 < 4) {
-#pragma unroll
-                        for (int db = 0; db < DB; ++db)
-#pragma unroll
-                            for (int t = 0; t < 2; ++t)
-                                tv[(st + 1) & 1][db][t] = lds_read_tr4_at(qb_base + taddr[db][t] + (st + 1) * 16 * ROWB);
-                    }
-#pragma unroll
-                    for (int db = 0; db < DB; ++db)
-                        acc[db] = mfma32(cat4(tv[st & 1][db][0], tv[st & 1][db][1]), dsf[st], acc[db]);
-                }
-            }
+        if (role == 0) {
+            if (live) score_stage(!full);
+        } else {
+            if (live_prev) grad_stage();
         }
-        t = tn; buf ^= 1;
+
+        if (new_group) cur_f = flags_of(gd_n, real_n, gn);
+        live_prev = live;
+        rotate(b);
+        g = gn; hh = hn; b = bn;
     }
 
     if (whole) {

@@ -87,7 +87,7 @@ __device__ __forceinline__ int4 ld_const4(const int32_t* p) {
 // makes both access patterns of the kernels bank-conflict free: 16 rows x one chunk (b128
 // MFMA operand reads) and 4 rows x 4 consecutive chunks (transpose reads).
 template <int CPR>
-__device__ __forceinline__ int swz(int r, int cc) {
+__host__ __device__ __forceinline__ constexpr int swz(int r, int cc) {
     return cc ^ ((((r & 3) << 2) | ((r >> 2) & 3)) & (CPR - 1));
 }
 
