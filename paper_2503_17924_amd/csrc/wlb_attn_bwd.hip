@@ -308,37 +308,55 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
     TileDma<D, GR, NW> dma;
     dma.init(wave, lane, q_row);
     const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
+    const uint32_t small_base = (uint32_t)(uintptr_t)(WLB_LDS char*)&small_s[0][0][0];
+    // The copies of a stage are issued with as little scalar work as possible (it sits between the
+    // barrier and the stage's first MFMA): the Q and dO descriptors span the whole tensors and the
+    // stage's row group and head go into the scalar offset (an address at or past the tensor's end
+    // still reads as zeros: the hardware compares offset + scalar offset with the size); everything
+    // that depends only on the wavefront is computed here.
+    BufRsrc q_rs, do_rs;
+    q_rs.init(p.q, q_total);
+    do_rs.init(p.d_o, q_total);
+    uint32_t dma_soff[TileDma<D, GR, NW>::PER], dma_lds[TileDma<D, GR, NW>::PER];
+#pragma unroll
+    for (int n = 0; n < TileDma<D, GR, NW>::PER; ++n) {
+        const uint32_t blk = (uint32_t)(wave * TileDma<D, GR, NW>::PER + n);
+        dma_soff[n] = uniform(blk * TileDma<D, GR, NW>::RPI * q_row * 2u);
+        dma_lds[n] = uniform(smem_base + blk * 1024u);
+    }
+    const uint32_t group_bytes = (uint32_t)GR * q_row * 2u;
     auto issue_stage = [&](int g, int h, int b) {
-        BufRsrc qrs, ors;
-        qrs.init(p.q + (size_t)h * D, q_total - (uint32_t)h * ROWB);
-        ors.init(p.d_o + (size_t)h * D, q_total - (uint32_t)h * ROWB);
-        dma.issue(qrs, smem_base + (uint32_t)((2 * b) * TILEB), g * GR, wave);
-        dma.issue(ors, smem_base + (uint32_t)((2 * b + 1) * TILEB), g * GR, wave);
+        const uint32_t so = uniform((uint32_t)g * group_bytes + (uint32_t)h * ROWB);
+        const uint32_t lo = uniform((uint32_t)b * (2 * TILEB));
+#pragma unroll
+        for (int n = 0; n < TileDma<D, GR, NW>::PER; ++n) {
+            dma_issue_1k(q_rs.r, dma_lds[n] + lo, dma.voff[n], so + dma_soff[n]);
+            dma_issue_1k(do_rs.r, dma_lds[n] + lo + TILEB, dma.voff[n], so + dma_soff[n]);
+        }
     };
     // Per-row scalars of a stage (visible key interval, log2-scaled LSE, delta) are copied
     // global->LDS asynchronously as well, by wavefront 0: no register load sits between the copies
     // and the compute, so nothing makes the compiler wait on vector memory while they are in
-    // flight.  Rows past n_q read as zeros (row_hi = 0: no visible key; their Q/dO rows are zero).
-    BufRsrc lo_rs, hi_rs;
+    // flight.  Rows past n_q read as zeros (row_hi = 0: no visible key; their Q/dO rows are zero);
+    // the LSE and delta descriptors are therefore per head (base + h * n_q, n_q entries).
+    BufRsrc lo_rs, hi_rs, ls_rs, dl_rs;
     lo_rs.init(p.row_lo, (uint32_t)p.n_q * 4u);
     hi_rs.init(p.row_hi, (uint32_t)p.n_q * 4u);
-    lo_rs.make_uniform();
-    hi_rs.make_uniform();
+    ls_rs.init(p.lse2, (uint32_t)p.n_q * 4u);
+    dl_rs.init(p.delta, (uint32_t)p.n_q * 4u);
+    const uint64_t lse_addr = (uint64_t)(uintptr_t)p.lse2, delta_addr = (uint64_t)(uintptr_t)p.delta;
     auto load_small = [&](int g, int h, int b) {
         if (wave == 0) {
-            BufRsrc ls_rs, dl_rs;
-            ls_rs.init(p.lse2 + (size_t)h * p.n_q, (uint32_t)p.n_q * 4u);
-            dl_rs.init(p.delta + (size_t)h * p.n_q, (uint32_t)p.n_q * 4u);
-            ls_rs.make_uniform();
-            dl_rs.make_uniform();
-            const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)(g * GR) * 4u);
-            auto lds_of = [&](const void* ptr) __attribute__((always_inline)) {
-                return (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)(WLB_LDS const void*)ptr);
-            };
-            dma_issue_256(ls_rs.r, lds_of(&small_s[b][0][0]), lane * 4, soff);
-            dma_issue_256(dl_rs.r, lds_of(&small_s[b][1][0]), lane * 4, soff);
-            dma_issue_256(lo_rs.r, lds_of(&small_s[b][2][0]), lane * 4, soff);
-            dma_issue_256(hi_rs.r, lds_of(&small_s[b][3][0]), lane * 4, soff);
+            const uint64_t ho = (uint64_t)(uint32_t)h * (uint32_t)p.n_q * 4u;
+            const uint64_t la = lse_addr + ho, da = delta_addr + ho;
+            ls_rs.r[0] = (int)(uint32_t)la; ls_rs.r[1] = (int)(uint32_t)((la >> 32) & 0xffffu);
+            dl_rs.r[0] = (int)(uint32_t)da; dl_rs.r[1] = (int)(uint32_t)((da >> 32) & 0xffffu);
+            const uint32_t soff = uniform((uint32_t)(g * GR) * 4u);
+            const uint32_t sl = uniform(small_base + (uint32_t)b * (4 * GR * 4));
+            dma_issue_256(ls_rs.r, sl, lane * 4, soff);
+            dma_issue_256(dl_rs.r, sl + GR * 4, lane * 4, soff);
+            dma_issue_256(lo_rs.r, sl + 2 * GR * 4, lane * 4, soff);
+            dma_issue_256(hi_rs.r, sl + 3 * GR * 4, lane * 4, soff);
         }
     };
 
@@ -365,7 +383,7 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
         const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
         taddr[db] = stage_base + (role == 0 ? TILEB : 0) + qq * ROWB + swz<CPR>(qq, dch) * 16 + (j16 & 1) * 8;
     }
-    uint32_t saddr = (uint32_t)(uintptr_t)(WLB_LDS char*)&small_s[0][0][0] + (uint32_t)rot0 * (4 * GR * 4) + half * 16;
+    uint32_t saddr = small_base + (uint32_t)rot0 * (4 * GR * 4) + half * 16;
     // score role: P buffer of its stage, gradient role: of the stage before
     uint32_t paddr = ((uint32_t)(uintptr_t)(WLB_LDS char*)pbuf + kblk * 4096 + lane * 16) ^ (role == 0 ? 0u : (uint32_t)PBYTES);
     // b = buffer of the stage the score role just ran

@@ -213,15 +213,9 @@ __global__ void __launch_bounds__(1024) plan_key_split_kernel(const int32_t* __r
     for (int kt = threadIdx.x; kt < n_key_tiles; kt += 1024) {
         const int span = key_range[2 * kt + 1] - key_range[2 * kt];
         int w = 1;
-#ifndef WLB_X_NOSPLIT
         while (w < G && (long long)span * (G / w) > thr && G % (2 * w) == 0) w *= 2;
-#endif
         ways[kt] = w;
-#ifdef WLB_X_SPANORDER
-        item_cost[kt] = span;
-#else
         item_cost[kt] = span * (G / w);
-#endif
     }
 }
 
