@@ -182,9 +182,8 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
         }
         constexpr int kb_base = cur * TILEB, vb_base = (2 + cur) * TILEB;
         const bool partial = (j < fb) || (j >= fe);
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            f32x16 s, dp;
+        // S^T and dP^T of a 32-key block (two independent accumulation chains)
+        auto scores = [&](int kb, f32x16& s, f32x16& dp) __attribute__((always_inline)) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
@@ -194,20 +193,20 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
                 s = mfma32(ka, qf[ks], s);
                 dp = mfma32(va, dof[ks], dp);
             }
-            float ds[16];
+        };
+        // dS^T = P^T o (dP^T - delta), in place of s
+        auto grads = [&](f32x16& s, const f32x16& dp) __attribute__((always_inline)) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], cs, -lsec)) * (dp[r] - dl);
+        };
+        auto mask = [&](int kb, f32x16& ds) __attribute__((always_inline)) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float pr = fast_exp2(fmaf(s[r], cs, -lsec));
-                ds[r] = pr * (dp[r] - dl);
+                const int key = j * BN + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                ds[r] = (key >= lo && key < hi) ? ds[r] : 0.f;
             }
-            if (partial) {
-                asm volatile("");   // keep the mask a branch
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = j * BN + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-                    ds[r] = (key >= lo && key < hi) ? ds[r] : 0.f;
-                }
-            }
+        };
+        auto update = [&](int kb, const f32x16& ds) __attribute__((always_inline)) {
             bf16x8 dsf[2];
             dsf[0] = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
             dsf[1] = pack8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
@@ -221,7 +220,25 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
                     acc[db] = mfma32(a, dsf[cc], acc[db]);
                 }
             }
+        };
+        // The vector-ALU work of a block runs beside MFMAs that do not depend on it: block 0's
+        // exponentials beside block 1's score MFMAs, block 1's beside block 0's dQ update.  The mask
+        // (only on a document's diagonal or edge) is a branch between those straight-line regions.
+        f32x16 s0, dp0, s1, dp1;
+        scores(0, s0, dp0);
+        scores(1, s1, dp1);
+        grads(s0, dp0);
+        if (partial) {
+            asm volatile("");   // keep the mask a branch
+            mask(0, s0);
         }
+        update(0, s0);
+        grads(s1, dp1);
+        if (partial) {
+            asm volatile("");
+            mask(1, s1);
+        }
+        update(1, s1);
     };
     for (int j = jb; j < je; j += 2) {
         tile_step(j, std::integral_constant<int, 0>{});
