@@ -234,6 +234,12 @@ typedef struct {
     size_t  off_key_ways;                /* int32 [n_key_tiles]: items per (key tile, KV head), by key tile */
     size_t  off_key_item_base;           /* int32 [n_key_tiles + 1]: first item of the tile of order rank r */
     size_t  off_key_slot_base;           /* int32 [n_key_tiles + 1]: first partial slot of the tile of rank r */
+    /* forward / dQ work: the query tiles in order, each repeated for every KV head, form one line of
+       work measured in key tiles (plus a fixed per-tile cost); row_gangs gangs of hq/hkv workgroups
+       take equal consecutive shares of it, so a tile cut by a share's end is finished by the next gang
+       and the parts are merged from fp32 partial results */
+    int32_t row_gangs;
+    size_t  off_fwd_prefix;              /* int64 [n_fwd_tiles + 1]: cost of the query tiles before order rank r */
     size_t  plan_bytes;
 } wlb_plan_layout;
 

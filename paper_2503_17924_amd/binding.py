@@ -53,6 +53,7 @@ class PlanLayout(C.Structure):
                 ("off_group_real", C.c_size_t), ("off_fwd_order", C.c_size_t), ("off_fwd_cost", C.c_size_t), ("off_key_order", C.c_size_t),
                 ("off_key_range", C.c_size_t), ("dkv_max_items", C.c_int32), ("dkv_max_partials", C.c_int32),
                 ("off_key_ways", C.c_size_t), ("off_key_item_base", C.c_size_t), ("off_key_slot_base", C.c_size_t),
+                ("row_gangs", C.c_int32), ("off_fwd_prefix", C.c_size_t),
                 ("plan_bytes", C.c_size_t)]
 
 

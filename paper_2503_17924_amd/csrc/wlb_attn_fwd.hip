@@ -2,8 +2,9 @@
 // causal inside a document, nothing across documents; Section 2.1 the data flow: one
 // context-parallel rank's query rows against the whole packed sequence's K/V).
 //
-// One workgroup = one query tile of 128 local rows x one query head, four wavefronts of 32
-// rows.  A wavefront keeps its bf16 Q operands, the running row max / sum and the transposed
+// A piece of work = one query tile of 128 local rows x one query head (or a part of its key
+// range), run by a workgroup of four wavefronts of 32 rows; the launch is a fixed set of
+// workgroups, each of which walks an equal share of all the work (see RowSched).  A wavefront keeps its bf16 Q operands, the running row max / sum and the transposed
 // output accumulator O^T[d][q] in registers.  Scores are computed transposed, S^T = K Q^T,
 // with the 32x32x16 bf16 MFMA: a lane then holds one query column and 16 key rows per block,
 // so the row max/sum are in-register reductions plus one exchange between the two lane
@@ -22,36 +23,25 @@ namespace wlb {
 struct FwdParams {
     const __bf16* q; const __bf16* k; const __bf16* v;
     __bf16* o; float* lse;
-    const int32_t* row_lo; const int32_t* row_hi; const int32_t* group; const int32_t* order;
+    const int32_t* row_lo; const int32_t* row_hi; const int32_t* group;
+    RowSched sched;            // which query tiles, heads and key ranges a workgroup works on
+    float* partial;            // partial results of the tiles cut at a gang boundary
     int n_q, t_kv, hq, hkv, n_groups, n_tiles;
     float scale_log2e, scale;
 };
 
-// Two workgroups per CU (two wavefronts per SIMD).  Work advances in blocks of 32 keys, each
-// one straight-line region: the MFMA pipe computes the scores of block i+1 and accumulates
-// O^T += V^T P^T of block i while the vector ALU exponentiates block i and reduces the row max
-// of block i+1 (on gfx950 the two overlap only inside one wavefront's instruction stream).
-// To let the score MFMAs run one block ahead without a third buffer, the K tiles are shifted
-// by half a tile against the V tiles: K tile j holds keys [64j+32, 64j+96), V tile j holds
-// keys [64j, 64j+64).
+// One piece of work: key tiles [pc.a, pc.b) of the pc.c the query tile pc.tile sees, for query head
+// pc.hk * G + pc.member.  A whole tile (pc.slot < 0) writes O and LSE; a part writes its
+// unnormalised accumulator, row sums and reference exponents as a partial result.
 template <int D>
-__global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
+__device__ __forceinline__ void fwd_piece(const FwdParams& p, char* smem, const RowPiece& pc) {
     constexpr int NW = 4, BM = 128, BN = 64;
     static_assert(BM == kFwdTileRows, "tile rows must match the schedule");
     constexpr int KS = D / 16, DB = D / 32, CPR = D / 8, ROWB = D * 2, TILEB = BN * ROWB;
 
-    __shared__ __attribute__((aligned(1024))) char smem[4 * TILEB];   // K0 | K1 | V0 | V1
-
     const int G = p.hq / p.hkv;
-    const int x = blockIdx.x & 7;
-    int y = blockIdx.x >> 3;
-    const int hh = y % G; y /= G;
-    const int hk = y % p.hkv;
-    const int c = y / p.hkv;
-    const int rank = c * 8 + x;
-    if (rank >= p.n_tiles) return;
-    const int tile = p.order[rank];
-    const int h = hk * G + hh;
+    const int tile = pc.tile, hk = pc.hk;
+    const int h = hk * G + pc.member;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
@@ -68,8 +58,10 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
     int jb = 0, je = 0, fb = 0, fe = 0;
     if (k_hi > k_lo) {
         jb = k_lo / BN; je = (k_hi + BN - 1) / BN;
-        fb = (max_lo + BN - 1) / BN; fe = min_hi / BN;
-        if (fe < fb) fe = fb;
+        // this piece's part of the tile's key tiles; the first kRowItemOverhead units of a tile's
+        // stretch of the work line stand for its fixed cost and hold no key tile
+        je = min(jb + max(pc.b - kRowItemOverhead, 0), je);
+        jb = jb + max(pc.a - kRowItemOverhead, 0);
     }
 
     const uint32_t kv_row = (uint32_t)p.hkv * D;
@@ -94,6 +86,20 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
     const int rc = in ? row : p.n_q - 1;
     const int lo = in ? p.row_lo[rc] : kPadLo;
     const int hi = in ? p.row_hi[rc] : 0;
+    // Key tiles every real row of this wavefront sees in full: only outside [fb, fe) does the
+    // wavefront mask (a tile of 128 rows that straddles a document boundary masks in the one
+    // wavefront that holds the boundary, not in all four).
+    {
+        int mlo = hi > 0 ? lo : 0, mhi = hi > 0 ? hi : kPadLo;
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) {
+            mlo = max(mlo, __shfl_xor(mlo, o));
+            mhi = min(mhi, __shfl_xor(mhi, o));
+        }
+        fb = uniform((mlo + BN - 1) / BN);
+        fe = uniform(mhi / BN);
+        if (fe < fb) fe = fb;
+    }
     bf16x8 qf[KS];
     {
         const __bf16* qp = p.q + ((size_t)rc * p.hq + h) * D + half * 8;
@@ -160,6 +166,18 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
         }
         return block_max(s);
     };
+    // a block outside the fully visible range: when every row sees either all of its 32 keys or none
+    // (rows of another document in the same wavefront) whole lanes are switched off; the element-wise
+    // mask is left to the blocks a row's interval really cuts (diagonal, document edges)
+    // (a lane is switched off by adding +inf to the reference its exponentials are taken against)
+    float bias_cur = 0.f, bias_next = 0.f;
+    auto mask_next = [&](f32x16& s, int key0, float mx) __attribute__((always_inline)) {
+        const bool none = (key0 + 32 <= lo) || (key0 >= hi);
+        const bool all = (key0 >= lo) && (key0 + 32 <= hi);
+        if (__any(!(none || all))) return mask_block(s, key0);
+        bias_next = none ? INFINITY : 0.f;
+        return none ? -INFINITY : mx;
+    };
     // rare path: move the reference up to the running max and rescale what has been accumulated
     auto move_reference = [&](float mx) __attribute__((always_inline)) {
         const float m_new = fmaxf(m, mx);
@@ -193,9 +211,10 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
     auto block_step = [&](int kimm, int vimm, int next_key0, bool next_partial) __attribute__((always_inline)) {
         f32x16 s_next = scores(kimm);
         float rs = 0.f;
+        const float mcb = mc + bias_cur;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const float e = fast_exp2(fmaf(s_cur[r], cs, -mc));
+            const float e = fast_exp2(fmaf(s_cur[r], cs, -mcb));
             s_cur[r] = e;
             rs += e;
         }
@@ -216,13 +235,15 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
         float mx = block_max(s_next);
         if (next_partial) {
             asm volatile("");
-            mx = mask_block(s_next, next_key0);
+            mx = mask_next(s_next, next_key0, mx);
         }
         if (__any(mx * cs > lim)) {
             asm volatile("");
             move_reference(mx);
         }
         s_cur = s_next;
+        bias_cur = bias_next;
+        bias_next = 0.f;
     };
     auto tile_step = [&](int j, auto cur_tag) __attribute__((always_inline)) {
         constexpr int cur = decltype(cur_tag)::value;
@@ -246,6 +267,26 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
     }
 
     const float lt = l + xhalf(l);
+    if (pc.slot >= 0) {
+        // part of a tile: accumulator [row][d], row sums and reference exponents (-inf: no key seen)
+        float* part = p.partial + (size_t)pc.slot * (BM * D + 2 * BM);
+        if (in) {
+            const int rl = wave * 32 + l32;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int d = db * 32 + r4 * 8 + half * 4;
+                    *reinterpret_cast<f32x4*>(part + (size_t)rl * D + d) =
+                        f32x4{acc[db][r4 * 4 + 0], acc[db][r4 * 4 + 1], acc[db][r4 * 4 + 2], acc[db][r4 * 4 + 3]};
+                }
+            if (half == 0) {
+                part[BM * D + rl] = lt;
+                part[BM * D + BM + rl] = (m == -INFINITY) ? -INFINITY : mc;
+            }
+        }
+        return;
+    }
     const bool live = in && (hi > 0) && (lt > 0.f);
     const float inv = live ? 1.0f / lt : 0.f;
     if (in) {
@@ -266,8 +307,84 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
     }
 }
 
+// Two workgroups per CU (two wavefronts per SIMD).  Work advances in blocks of 32 keys, each
+// one straight-line region: the MFMA pipe computes the scores of block i+1 and accumulates
+// O^T += V^T P^T of block i while the vector ALU exponentiates block i and reduces the row max
+// of block i+1 (on gfx950 the two overlap only inside one wavefront's instruction stream).
+// To let the score MFMAs run one block ahead without a third buffer, the K tiles are shifted
+// by half a tile against the V tiles: K tile j holds keys [64j+32, 64j+96), V tile j holds
+// keys [64j, 64j+64).  A workgroup walks its gang's share of the work line piece by piece.
+template <int D>
+__global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
+    __shared__ __attribute__((aligned(1024))) char smem[4 * 64 * D * 2];   // K0 | K1 | V0 | V1
+    RowWalk walk;
+    walk.start(p.sched, (int)blockIdx.x);
+    RowPiece pc;
+    while (walk.next(p.sched, pc)) fwd_piece<D>(p, smem, pc);
+}
+
+// Combines the partial results of a query tile that was cut at gang boundaries.  One workgroup per
+// (gang, member): it acts if its gang's last piece is the first part of a tile, and then takes
+// that part and the following gangs' first pieces.  With reference exponents e_i (log2 units), row
+// sums l_i and accumulators A_i:  E = max e_i,  L = sum l_i 2^(e_i - E),  O = sum A_i 2^(e_i - E) / L,
+// LSE = (E + log2 L) ln 2.
+template <int D>
+__global__ void __launch_bounds__(256) fwd_merge_kernel(const FwdParams p) {
+    constexpr int BM = kFwdTileRows, PF = BM * D + 2 * BM, V4 = D / 4;
+    const RowSched& s = p.sched;
+    const int gang = (int)blockIdx.x / s.G, member = (int)blockIdx.x % s.G;
+    const long long W = s.hkv * ld_const64(s.prefix + s.n_tiles);
+    const long long w0 = s.share_begin(W, gang), w1 = s.share_begin(W, gang + 1);
+    if (w0 >= w1) return;
+    int r, hk;
+    RowWalk::locate(s, w1 - 1, r, hk);
+    const long long p0 = ld_const64(s.prefix + r);
+    const long long c = ld_const64(s.prefix + r + 1) - p0;
+    const long long st = s.hkv * p0 + hk * c;
+    if (st < w0 || w1 - st >= c) return;        // the gang's last piece is not the first part of a cut tile
+    // parts: this gang's last piece, then the first piece of every later gang whose (non-empty) share
+    // begins inside the tile
+    const long long tile_end = st + c;
+    const int tile = ld_const(s.order + r);
+    const int h = hk * s.G + member;
+    const float* first = p.partial + ((size_t)(2 * gang + 1) * s.G + member) * PF;
+    // calls f(part) for every later part
+    auto later_parts = [&](auto f) __attribute__((always_inline)) {
+        for (int g2 = gang + 1; g2 < s.n_gangs; ++g2) {
+            const long long b0 = s.share_begin(W, g2), b1 = s.share_begin(W, g2 + 1);
+            if (b0 >= tile_end) break;
+            if (b1 > b0) f(p.partial + ((size_t)(2 * g2) * s.G + member) * PF);
+        }
+    };
+    for (int e = threadIdx.x; e < BM * V4; e += 256) {
+        const int rl = e / V4, d4 = e % V4;
+        const int row = tile * BM + rl;
+        if (row >= p.n_q) continue;
+        float E = first[BM * D + BM + rl];
+        later_parts([&](const float* pp) { E = fmaxf(E, pp[BM * D + BM + rl]); });
+        float L = 0.f;
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
+        auto add = [&](const float* pp) __attribute__((always_inline)) {
+            const float ei = pp[BM * D + BM + rl];
+            if (ei == -INFINITY) return;
+            const float wgt = fast_exp2(ei - E);
+            L += wgt * pp[BM * D + rl];
+            o += wgt * *reinterpret_cast<const f32x4*>(pp + (size_t)rl * D + d4 * 4);
+        };
+        if (E > -INFINITY) {
+            add(first);
+            later_parts(add);
+        }
+        const bool live = p.row_hi[row] > 0 && L > 0.f;
+        const float inv = live ? 1.0f / L : 0.f;
+        *reinterpret_cast<bf16x4*>(p.o + ((size_t)row * p.hq + h) * D + d4 * 4) =
+            live ? pack4(o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv) : pack4(0.f, 0.f, 0.f, 0.f);
+        if (d4 == 0) p.lse[(size_t)h * p.n_q + row] = live ? (E + __log2f(L)) * 0.6931471805599453f : -INFINITY;
+    }
+}
+
 wlb_status launch_fwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const void* q, const void* k,
-                      const void* v, void* o, float* lse, char* ws, void* stream_) {
+                      const void* v, void* o, float* lse, char* ws, size_t off_row_partial, void* stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     FwdParams p;
     p.q = (const __bf16*)q; p.k = (const __bf16*)k; p.v = (const __bf16*)v;
@@ -275,14 +392,23 @@ wlb_status launch_fwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.row_lo = (const int32_t*)(ws + L.off_row_lo);
     p.row_hi = (const int32_t*)(ws + L.off_row_hi);
     p.group = (const int32_t*)(ws + L.off_group);
-    p.order = (const int32_t*)(ws + L.off_fwd_order);
+    p.sched.prefix = (const long long*)(ws + L.off_fwd_prefix);
+    p.sched.order = (const int32_t*)(ws + L.off_fwd_order);
+    p.sched.n_tiles = L.n_fwd_tiles; p.sched.hkv = d.hkv; p.sched.G = d.hq / d.hkv; p.sched.n_gangs = L.row_gangs;
+    p.sched.w_first = kRowShareFirst; p.sched.w_second = kRowShareSecond;
+    p.partial = (float*)(ws + off_row_partial);
     p.n_q = d.n_q; p.t_kv = d.t_kv; p.hq = d.hq; p.hkv = d.hkv;
     p.n_groups = L.n_groups; p.n_tiles = L.n_fwd_tiles;
     p.scale = d.scale;
     p.scale_log2e = d.scale * 1.4426950408889634f;
-    const unsigned grid = (unsigned)((L.n_fwd_tiles + 7) / 8) * 8u * (unsigned)d.hq;
-    if (d.head_dim == 128) fwd_kernel<128><<<grid, 256, 0, stream>>>(p);
-    else fwd_kernel<64><<<grid, 256, 0, stream>>>(p);
+    const unsigned grid = (unsigned)L.row_gangs * (unsigned)(d.hq / d.hkv);
+    if (d.head_dim == 128) {
+        fwd_kernel<128><<<grid, 256, 0, stream>>>(p);
+        fwd_merge_kernel<128><<<grid, 256, 0, stream>>>(p);
+    } else {
+        fwd_kernel<64><<<grid, 256, 0, stream>>>(p);
+        fwd_merge_kernel<64><<<grid, 256, 0, stream>>>(p);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(WLB_ERR_HIP, "forward launch: %s", hipGetErrorString(e));
     return WLB_OK;

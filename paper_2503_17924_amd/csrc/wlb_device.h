@@ -82,6 +82,81 @@ __device__ __forceinline__ int4 ld_const4(const int32_t* p) {
     return int4{v[0], v[1], v[2], v[3]};
 }
 
+__device__ __forceinline__ long long ld_const64(const long long* p) {
+    return *reinterpret_cast<const WLB_CONST long long*>((uintptr_t)p);
+}
+
+// ------------------------------------------------------------------------------------------
+// Work schedule of the forward and dQ kernels.  The query tiles in order (heaviest first), each
+// repeated for every KV head, form one line of work measured in key tiles (each tile's stretch
+// begins with a few units that stand for its fixed cost).  A launch has n_gangs gangs of G = hq / hkv workgroups (one per query head of a KV
+// head); the gangs take consecutive shares of the line, so a gang's load does not depend on the
+// tiles' sizes.  The shares of the first half of the gangs are larger than those of the second
+// half (w_first : w_second): with two workgroups per compute unit the workgroups of the first half
+// of the launch are the older wavefronts of their SIMDs, win issue arbitration and advance faster.  A tile cut by a share's end is continued by
+// the next gang; the pieces of such a tile leave fp32 partial results that a merge kernel
+// combines.  Workgroup b is member (b / 8) % G of gang ((b / 8) / G) * 8 + b % 8: consecutive
+// workgroups go to consecutive XCDs, so a gang's members share an XCD (and its L2 copy of K/V).
+struct RowSched {
+    const long long* prefix;   // [n_tiles + 1] cost of the query tiles before order rank r
+    const int32_t* order;      // [n_tiles]
+    int n_tiles, hkv, G, n_gangs;
+    int w_first, w_second;     // relative shares of a gang of the first / second half of the gangs
+    // first unit of gang g's share of a line of W units (g = n_gangs: W)
+    __device__ __forceinline__ long long share_begin(long long W, int g) const {
+        const int half = n_gangs / 2;
+        const long long cum = g <= half ? (long long)g * w_first : (long long)half * w_first + (long long)(g - half) * w_second;
+        const long long tot = (long long)half * w_first + (long long)(n_gangs - half) * w_second;
+        return W * cum / tot;
+    }
+};
+struct RowPiece {
+    int tile, hk, member;
+    int a, b, c;               // units [a, b) of the tile's c
+    int slot;                  // partial result index, -1 for a whole tile (a == 0 and b == c)
+};
+struct RowWalk {
+    long long pos, end;
+    int r, hk, gang, member;
+    __device__ __forceinline__ void start(const RowSched& s, int block) {
+        const int x = block & 7, i = block >> 3;
+        member = i % s.G;
+        gang = (i / s.G) * 8 + x;
+        const long long W = s.hkv * ld_const64(s.prefix + s.n_tiles);
+        pos = s.share_begin(W, gang);
+        end = s.share_begin(W, gang + 1);
+        r = 0; hk = 0;
+        if (pos >= end) return;
+        locate(s, pos, r, hk);
+    }
+    // the (order rank, KV head) whose stretch of the line contains unit u < W
+    __device__ static __forceinline__ void locate(const RowSched& s, long long u, int& r, int& hk) {
+        int lo = 0, hi = s.n_tiles;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (s.hkv * ld_const64(s.prefix + mid) <= u) lo = mid; else hi = mid;
+        }
+        const long long p0 = ld_const64(s.prefix + lo), c = ld_const64(s.prefix + lo + 1) - p0;
+        r = lo;
+        hk = (int)((u - s.hkv * p0) / c);
+    }
+    __device__ __forceinline__ bool next(const RowSched& s, RowPiece& pc) {
+        if (pos >= end) return false;
+        const long long p0 = ld_const64(s.prefix + r);
+        const int c = (int)(ld_const64(s.prefix + r + 1) - p0);
+        const long long st = s.hkv * p0 + (long long)hk * c;
+        pc.tile = ld_const(s.order + r);
+        pc.hk = hk; pc.member = member; pc.c = c;
+        pc.a = (int)(pos - st);
+        pc.b = (int)((end - st < c) ? end - st : c);
+        // a piece that starts inside a tile is its gang's first, one that ends inside a tile its last
+        pc.slot = (pc.a == 0 && pc.b == c) ? -1 : ((pc.a > 0 ? 2 * gang : 2 * gang + 1) * s.G + member);
+        pos = st + c;
+        if (++hk == s.hkv) { hk = 0; ++r; }
+        return true;
+    }
+};
+
 // XOR swizzle of the 16-byte chunks of an unpadded row-major LDS tile whose rows hold CPR
 // chunks: logical chunk cc of row r is stored at chunk swz(r, cc).  With 256-byte rows it
 // makes both access patterns of the kernels bank-conflict free: 16 rows x one chunk (b128

@@ -25,6 +25,25 @@ constexpr int kDkvSplit = WLB_DKV_SPLIT;      // a dK/dV item is at most 1/kDkvS
 
 // compute units of the GPU (256 when none is present: layout queries on the host)
 int compute_units();
+// Forward and dQ run as a fixed set of workgroups, two per compute unit, in gangs of the
+// G = hq / hkv query heads that share a KV head (a gang's workgroups sit on one XCD and walk the
+// same K/V tiles side by side).  Number of gangs:
+inline int row_gangs(int hq, int hkv, int cus) {
+    const int per_xcd = (2 * cus / kLists) / (hq / hkv);
+    return kLists * (per_xcd > 0 ? per_xcd : 1);
+}
+// fixed cost of a query tile (loading Q, the first copies, the output) in units of one key tile's work
+constexpr int kRowItemOverhead = 6;
+// relative work shares of a gang of the first and of the second half of a forward / dQ launch
+#ifndef WLB_ROW_SHARE_FIRST
+#define WLB_ROW_SHARE_FIRST 58
+#endif
+constexpr int kRowShareFirst = WLB_ROW_SHARE_FIRST, kRowShareSecond = 100 - WLB_ROW_SHARE_FIRST;
+// floats of one partial result of a query tile and head: 128 x D accumulator, then 128 row sums and
+// 128 reference exponents
+inline size_t row_partial_floats(int head_dim) { return (size_t)kFwdTileRows * head_dim + 2 * kFwdTileRows; }
+// bytes of the partial results of the query tiles that are cut at a gang boundary: two per gang and member
+size_t row_partial_bytes(const wlb_attn_desc& d, const wlb_plan_layout& L);
 // bytes of the dK/dV partial results that follow delta / lse2 in the backward workspace
 size_t dkv_partial_bytes(const wlb_attn_desc& d, const wlb_plan_layout& L);
 
@@ -36,7 +55,7 @@ void plan_layout(const wlb_attn_desc& d, wlb_plan_layout* L);
 wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const int32_t* q_idx,
                        const int32_t* cu_seqlens_k, char* ws, void* stream);
 wlb_status launch_fwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const void* q, const void* k,
-                      const void* v, void* o, float* lse, char* ws, void* stream);
+                      const void* v, void* o, float* lse, char* ws, size_t off_row_partial, void* stream);
 wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const void* q, const void* k,
                       const void* v, const void* o, const float* lse, const void* d_o, void* dq,
                       void* dk, void* dv, char* ws, size_t off_delta, void* stream);

@@ -51,6 +51,10 @@ size_t dkv_partial_bytes(const wlb_attn_desc& d, const wlb_plan_layout& L) {
     return (size_t)L.dkv_max_partials * (2 * (size_t)kBwdKeyTile * d.head_dim * sizeof(float));
 }
 
+size_t row_partial_bytes(const wlb_attn_desc& d, const wlb_plan_layout& L) {
+    return (size_t)2 * L.row_gangs * (d.hq / d.hkv) * row_partial_floats(d.head_dim) * sizeof(float);
+}
+
 void plan_layout(const wlb_attn_desc& d, wlb_plan_layout* L) {
     L->group_rows = kGroupRows;
     L->n_groups = (d.n_q + kGroupRows - 1) / kGroupRows;
@@ -77,6 +81,8 @@ void plan_layout(const wlb_attn_desc& d, wlb_plan_layout* L) {
     L->off_key_ways = take(sizeof(int32_t) * L->n_key_tiles);
     L->off_key_item_base = take(sizeof(int32_t) * (L->n_key_tiles + 1));
     L->off_key_slot_base = take(sizeof(int32_t) * (L->n_key_tiles + 1));
+    L->row_gangs = row_gangs(d.hq, d.hkv, compute_units());
+    L->off_fwd_prefix = take(sizeof(int64_t) * (L->n_fwd_tiles + 1));
     L->plan_bytes = off;
 }
 
@@ -255,6 +261,31 @@ __global__ void __launch_bounds__(1024) plan_key_bases_kernel(const int32_t* __r
     if (threadIdx.x == 1023) { item_base[n_key_tiles] = s_items[1023]; slot_base[n_key_tiles] = s_slots[1023]; }
 }
 
+// One workgroup.  prefix[r] = cost (key tiles + the fixed kRowItemOverhead each) of the query tiles of order rank < r.
+__global__ void __launch_bounds__(1024) plan_fwd_prefix_kernel(const int32_t* __restrict__ order,
+                                                               const int32_t* __restrict__ cost, int n_tiles,
+                                                               long long* __restrict__ prefix) {
+    __shared__ long long s_sum[1024];
+    const int per = (n_tiles + 1023) / 1024;
+    const int r0 = min((int)threadIdx.x * per, n_tiles), r1 = min(r0 + per, n_tiles);
+    long long mine = 0;
+    for (int r = r0; r < r1; ++r) mine += cost[order[r]] + kRowItemOverhead;
+    s_sum[threadIdx.x] = mine;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        const long long add = (int)threadIdx.x >= o ? s_sum[threadIdx.x - o] : 0;
+        __syncthreads();
+        s_sum[threadIdx.x] += add;
+        __syncthreads();
+    }
+    long long run = s_sum[threadIdx.x] - mine;
+    for (int r = r0; r < r1; ++r) {
+        prefix[r] = run;
+        run += cost[order[r]] + kRowItemOverhead;
+    }
+    if (threadIdx.x == 1023) prefix[n_tiles] = s_sum[1023];
+}
+
 wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const int32_t* q_idx,
                        const int32_t* cu_seqlens_k, char* ws, void* stream_) {
     hipStream_t stream = (hipStream_t)stream_;
@@ -274,6 +305,7 @@ wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const i
     plan_key_tiles_kernel<<<(L.n_key_tiles + 3) / 4, 256, 0, stream>>>(group, L.n_groups, L.n_key_tiles,
                                                                        kBwdKeyTile, d.t_kv, key_range, key_cost);
     plan_order_kernel<<<(L.n_fwd_tiles + 255) / 256, 256, 0, stream>>>(fwd_cost, L.n_fwd_tiles, fwd_order);
+    plan_fwd_prefix_kernel<<<1, 1024, 0, stream>>>(fwd_order, fwd_cost, L.n_fwd_tiles, (long long*)(ws + L.off_fwd_prefix));
     int32_t* key_ways = (int32_t*)(ws + L.off_key_ways);
     plan_key_split_kernel<<<1, 1024, 0, stream>>>(key_range, L.n_key_tiles, d.hq, d.hkv, compute_units(), key_ways, key_cost);
     plan_order_kernel<<<(L.n_key_tiles + 255) / 256, 256, 0, stream>>>(key_cost, L.n_key_tiles, key_order);
@@ -296,8 +328,8 @@ extern "C" wlb_status wlb_attn_workspace_size(const wlb_attn_desc* desc, size_t*
     if (!fwd_bytes || !bwd_bytes) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_workspace_size: null output");
     wlb_plan_layout L;
     plan_layout(*desc, &L);
-    *fwd_bytes = L.plan_bytes;
-    *bwd_bytes = L.plan_bytes + delta_bytes(*desc) + dkv_partial_bytes(*desc, L);
+    *fwd_bytes = L.plan_bytes + row_partial_bytes(*desc, L);
+    *bwd_bytes = L.plan_bytes + delta_bytes(*desc) + dkv_partial_bytes(*desc, L) + row_partial_bytes(*desc, L);
     return WLB_OK;
 }
 
@@ -328,11 +360,12 @@ extern "C" wlb_status wlb_attn_fwd(const wlb_attn_desc* desc, const void* q, con
     if (!reuse && (!q_idx || !cu_seqlens_k)) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_fwd: null q_idx/cu_seqlens_k");
     wlb_plan_layout L;
     plan_layout(*desc, &L);
-    if (workspace_bytes < L.plan_bytes)
-        return fail(WLB_ERR_BUFFER_TOO_SMALL, "wlb_attn_fwd: workspace %zu < %zu bytes", workspace_bytes, L.plan_bytes);
+    const size_t need = L.plan_bytes + row_partial_bytes(*desc, L);
+    if (workspace_bytes < need)
+        return fail(WLB_ERR_BUFFER_TOO_SMALL, "wlb_attn_fwd: workspace %zu < %zu bytes", workspace_bytes, need);
     if (!reuse)
         if (wlb_status st = launch_plan(*desc, L, q_idx, cu_seqlens_k, (char*)workspace, stream)) return st;
-    return launch_fwd(*desc, L, q, k, v, o, lse, (char*)workspace, stream);
+    return launch_fwd(*desc, L, q, k, v, o, lse, (char*)workspace, L.plan_bytes, stream);
 }
 
 extern "C" wlb_status wlb_attn_bwd(const wlb_attn_desc* desc, const void* q, const void* k, const void* v,
@@ -346,7 +379,7 @@ extern "C" wlb_status wlb_attn_bwd(const wlb_attn_desc* desc, const void* q, con
     if (!reuse && (!q_idx || !cu_seqlens_k)) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_bwd: null q_idx/cu_seqlens_k");
     wlb_plan_layout L;
     plan_layout(*desc, &L);
-    const size_t need = L.plan_bytes + delta_bytes(*desc) + dkv_partial_bytes(*desc, L);
+    const size_t need = L.plan_bytes + delta_bytes(*desc) + dkv_partial_bytes(*desc, L) + row_partial_bytes(*desc, L);
     if (workspace_bytes < need)
         return fail(WLB_ERR_BUFFER_TOO_SMALL, "wlb_attn_bwd: workspace %zu < %zu bytes", workspace_bytes, need);
     if (!reuse)

@@ -79,6 +79,9 @@ def test_forward_is_deterministic_and_plan_reuse_changes_nothing():
     assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
 
 
+ROW_ITEM_OVERHEAD = 6     # units of fixed cost per query tile in the forward / dQ work line
+
+
 def test_schedule_tables():
     """The schedule in the workspace: row intervals equal the definition, group hulls cover
     their rows, fully visible ranges are visible to every real row, orders are permutations
@@ -119,6 +122,11 @@ def test_schedule_tables():
         cost = arr(lay.off_fwd_cost, lay.n_fwd_tiles)
         assert sorted(order.tolist()) == list(range(lay.n_fwd_tiles))
         assert (np.diff(cost[order]) <= 0).all()
+        # forward / dQ work line: running sum, in order, of key tiles + the fixed per-tile cost
+        prefix = ws[lay.off_fwd_prefix:lay.off_fwd_prefix + 8 * (lay.n_fwd_tiles + 1)].view(np.int64)
+        assert prefix[0] == 0 and (np.diff(prefix) == cost[order] + ROW_ITEM_OVERHEAD).all()
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        assert lay.row_gangs == 8 * max(1, (2 * n_cu // 8) // (c.hq // c.hkv))
         korder = arr(lay.off_key_order, lay.n_key_tiles)
         krange = arr(lay.off_key_range, 2 * lay.n_key_tiles).reshape(-1, 2)
         assert sorted(korder.tolist()) == list(range(lay.n_key_tiles))
@@ -146,7 +154,6 @@ def test_schedule_tables():
         assert item_base[-1] <= lay.dkv_max_items and slot_base[-1] <= lay.dkv_max_partials
         # no item is heavier than the threshold unless it is already a single head
         total = int(span.sum()) * c.hq
-        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
         assert (icost[ways < g_heads] <= max(16, -(-total // (8 * n_cu)))).all()
 
 
