@@ -6,10 +6,11 @@
 // dK/dV summed over the query heads that share a KV head.  As in all-gather context
 // parallelism (Section 2.1) dK/dV hold only the calling rank's rows' contribution.
 //
-// Four kernels, no atomics, deterministic:
+// Five kernels, no atomics, deterministic:
 //   delta_kernel      delta[h][i] = sum_d dO*O and the log2-scaled LSE copy (0 / +inf for padding rows)
-//   dq_kernel         query-stationary, same tiling as the forward: S^T and dP^T per lane column,
-//                     dQ^T += K^T dS^T with K^T read from LDS by transpose reads
+//   dq_kernel         query-stationary, same tiling and work schedule as the forward: S^T and dP^T
+//                     per lane column, dQ^T += K^T dS^T with K^T read from LDS by transpose reads
+//   dq_merge_kernel   sums the fp32 partial dQ of query tiles cut at a gang boundary
 //   dkv_kernel        key-stationary: a work item owns 128 keys of one KV head and streams the row
 //                     groups that can see them through LDS for some or all query heads of the KV
 //                     group; dK^T, dV^T stay in registers until the single final store
@@ -38,6 +39,8 @@ struct BwdParams {
     const int32_t* fwd_order; const int32_t* key_order; const int32_t* key_range;
     const int32_t* key_ways; const int32_t* key_item_base; const int32_t* key_slot_base;
     float* partial;
+    RowSched sched;            // dQ: which query tiles, heads and key ranges a workgroup works on
+    float* row_partial;        // dQ: partial results of the tiles cut at a gang boundary
     int n_q, t_kv, hq, hkv, n_groups, n_tiles, n_key_tiles;
     float scale_log2e, scale;
 };
@@ -75,23 +78,14 @@ __global__ void __launch_bounds__(256) delta_kernel(const BwdParams p) {
 // dS^T = P^T o (dP^T - delta) in registers and accumulates dQ^T += K^T dS^T with K^T read
 // from the same swizzled K tile by transpose reads.
 template <int D>
-__global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
+__device__ __forceinline__ void dq_piece(const BwdParams& p, char* smem, const RowPiece& pc) {
     constexpr int NW = 4, BM = 128, BN = 64;
     static_assert(BM == kFwdTileRows, "tile rows must match the schedule");
     constexpr int KS = D / 16, DB = D / 32, CPR = D / 8, ROWB = D * 2, TILEB = BN * ROWB;
 
-    __shared__ __attribute__((aligned(1024))) char smem[4 * TILEB];   // K0 | K1 | V0 | V1
-
     const int G = p.hq / p.hkv;
-    const int x = blockIdx.x & 7;
-    int y = blockIdx.x >> 3;
-    const int hh = y % G; y /= G;
-    const int hk = y % p.hkv;
-    const int c = y / p.hkv;
-    const int rank = c * 8 + x;
-    if (rank >= p.n_tiles) return;
-    const int tile = p.fwd_order[rank];
-    const int h = hk * G + hh;
+    const int tile = pc.tile, hk = pc.hk;
+    const int h = hk * G + pc.member;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
@@ -108,8 +102,10 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
     int jb = 0, je = 0, fb = 0, fe = 0;
     if (k_hi > k_lo) {
         jb = k_lo / BN; je = (k_hi + BN - 1) / BN;
-        fb = (max_lo + BN - 1) / BN; fe = min_hi / BN;
-        if (fe < fb) fe = fb;
+        // this piece's part of the tile's key tiles (the first kRowItemOverhead units of a tile's
+        // stretch of the work line stand for its fixed cost)
+        je = min(jb + max(pc.b - kRowItemOverhead, 0), je);
+        jb = jb + max(pc.a - kRowItemOverhead, 0);
     }
 
     const uint32_t kv_row = (uint32_t)p.hkv * D;
@@ -121,6 +117,7 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
     dma.init(wave, lane, kv_row);
     const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
     auto tile_ptr = [&](int which) { return smem_base + (uint32_t)(which * TILEB); };
+    __syncthreads();            // every wavefront has left the tiles of the piece before
     if (jb < je) {
         dma.issue(krs, tile_ptr(0), jb * BN, wave);
         dma.issue(vrs, tile_ptr(2), jb * BN, wave);
@@ -132,6 +129,18 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
     const int lo = in ? p.row_lo[rc] : kPadLo;
     const int hi = in ? p.row_hi[rc] : 0;
     const bool real = hi > 0;
+    // key tiles every real row of this wavefront sees in full: only outside [fb, fe) it masks
+    {
+        int mlo = real ? lo : 0, mhi = real ? hi : kPadLo;
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) {
+            mlo = max(mlo, __shfl_xor(mlo, o));
+            mhi = min(mhi, __shfl_xor(mhi, o));
+        }
+        fb = uniform((mlo + BN - 1) / BN);
+        fe = uniform(mhi / BN);
+        if (fe < fb) fe = fb;
+    }
     // padding rows: zero operands and LSE = +inf make P, dS and dQ exactly 0
     const float lsec = real ? p.lse[(size_t)h * p.n_q + rc] * 1.4426950408889634f : INFINITY;
     const float dl = real ? p.delta[(size_t)h * p.n_q + rc] : 0.f;
@@ -194,10 +203,20 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
                 dp = mfma32(va, dof[ks], dp);
             }
         };
-        // dS^T = P^T o (dP^T - delta), in place of s
-        auto grads = [&](f32x16& s, const f32x16& dp) __attribute__((always_inline)) {
+        // dS^T = P^T o (dP^T - delta), in place of s; ls = the row's LSE, or +inf to switch the lane off
+        auto grads = [&](f32x16& s, const f32x16& dp, float ls) __attribute__((always_inline)) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], cs, -lsec)) * (dp[r] - dl);
+            for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], cs, -ls)) * (dp[r] - dl);
+        };
+        // a block outside the fully visible range: rows that see none of its 32 keys (rows of another
+        // document in the same wavefront) are switched off as whole lanes; the element-wise mask is
+        // needed only where a row's interval cuts the block (diagonal, document edges)
+        auto classify = [&](int kb, float& ls, bool& elementwise) __attribute__((always_inline)) {
+            const int key0 = j * BN + kb * 32;
+            const bool none = (key0 + 32 <= lo) || (key0 >= hi);
+            const bool all = (key0 >= lo) && (key0 + 32 <= hi);
+            elementwise = __any(!(none || all));
+            ls = none ? INFINITY : lsec;
         };
         auto mask = [&](int kb, f32x16& ds) __attribute__((always_inline)) {
 #pragma unroll
@@ -225,16 +244,22 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
         // exponentials beside block 1's score MFMAs, block 1's beside block 0's dQ update.  The mask
         // (only on a document's diagonal or edge) is a branch between those straight-line regions.
         f32x16 s0, dp0, s1, dp1;
+        float ls0 = lsec, ls1 = lsec;
+        bool em0 = false, em1 = false;
+        if (partial) {
+            classify(0, ls0, em0);
+            classify(1, ls1, em1);
+        }
         scores(0, s0, dp0);
         scores(1, s1, dp1);
-        grads(s0, dp0);
-        if (partial) {
+        grads(s0, dp0, ls0);
+        if (em0) {
             asm volatile("");   // keep the mask a branch
             mask(0, s0);
         }
         update(0, s0);
-        grads(s1, dp1);
-        if (partial) {
+        grads(s1, dp1, ls1);
+        if (em1) {
             asm volatile("");
             mask(1, s1);
         }
@@ -245,6 +270,22 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
         if (j + 1 < je) tile_step(j + 1, std::integral_constant<int, 1>{});
     }
 
+    if (pc.slot >= 0) {
+        // part of a tile: unscaled fp32 dQ [row][d], summed by dq_merge_kernel
+        float* part = p.row_partial + (size_t)pc.slot * (BM * D + 2 * BM);
+        if (in) {
+            const int rl = wave * 32 + l32;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int d = db * 32 + r4 * 8 + half * 4;
+                    *reinterpret_cast<f32x4*>(part + (size_t)rl * D + d) =
+                        f32x4{acc[db][r4 * 4 + 0], acc[db][r4 * 4 + 1], acc[db][r4 * 4 + 2], acc[db][r4 * 4 + 3]};
+                }
+        }
+        return;
+    }
     if (in) {
         __bf16* op = p.dq + ((size_t)row * p.hq + h) * D;
 #pragma unroll
@@ -258,6 +299,54 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
                 else out = pack4(0.f, 0.f, 0.f, 0.f);
                 *reinterpret_cast<bf16x4*>(op + d) = out;
             }
+    }
+}
+
+// dQ: a fixed set of workgroups, each walking its gang's share of the work line (see RowSched).
+template <int D>
+__global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
+    __shared__ __attribute__((aligned(1024))) char smem[4 * 64 * D * 2];   // K0 | K1 | V0 | V1
+    RowWalk walk;
+    walk.start(p.sched, (int)blockIdx.x);
+    RowPiece pc;
+    while (walk.next(p.sched, pc)) dq_piece<D>(p, smem, pc);
+}
+
+// Sums the partial dQ of a query tile that was cut at gang boundaries.  One workgroup per
+// (gang, member): it acts if its gang's last piece is the first part of a tile, and then takes
+// that part and the first piece of every later gang whose (non-empty) share begins inside the tile.
+template <int D>
+__global__ void __launch_bounds__(256) dq_merge_kernel(const BwdParams p) {
+    constexpr int BM = kFwdTileRows, PF = BM * D + 2 * BM, V4 = D / 4;
+    const RowSched& s = p.sched;
+    const int gang = (int)blockIdx.x / s.G, member = (int)blockIdx.x % s.G;
+    const long long W = s.hkv * ld_const64(s.prefix + s.n_tiles);
+    const long long w0 = s.share_begin(W, gang), w1 = s.share_begin(W, gang + 1);
+    if (w0 >= w1) return;
+    int r, hk;
+    RowWalk::locate(s, w1 - 1, r, hk);
+    const long long p0 = ld_const64(s.prefix + r);
+    const long long c = ld_const64(s.prefix + r + 1) - p0;
+    const long long st = s.hkv * p0 + hk * c;
+    if (st < w0 || w1 - st >= c) return;        // the gang's last piece is not the first part of a cut tile
+    const long long tile_end = st + c;
+    const int tile = ld_const(s.order + r);
+    const int h = hk * s.G + member;
+    const float* first = p.row_partial + ((size_t)(2 * gang + 1) * s.G + member) * PF;
+    for (int e = threadIdx.x; e < BM * V4; e += 256) {
+        const int rl = e / V4, d4 = e % V4;
+        const int row = tile * BM + rl;
+        if (row >= p.n_q) continue;
+        f32x4 sum = *reinterpret_cast<const f32x4*>(first + (size_t)rl * D + d4 * 4);
+        for (int g2 = gang + 1; g2 < s.n_gangs; ++g2) {
+            const long long b0 = s.share_begin(W, g2), b1 = s.share_begin(W, g2 + 1);
+            if (b0 >= tile_end) break;
+            if (b1 > b0)
+                sum += *reinterpret_cast<const f32x4*>(p.row_partial + ((size_t)(2 * g2) * s.G + member) * PF + (size_t)rl * D + d4 * 4);
+        }
+        const bool real = p.row_hi[row] > 0;
+        *reinterpret_cast<bf16x4*>(p.dq + ((size_t)row * p.hq + h) * D + d4 * 4) =
+            real ? pack4(sum[0] * p.scale, sum[1] * p.scale, sum[2] * p.scale, sum[3] * p.scale) : pack4(0.f, 0.f, 0.f, 0.f);
     }
 }
 
@@ -721,6 +810,11 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.key_item_base = (const int32_t*)(ws + L.off_key_item_base);
     p.key_slot_base = (const int32_t*)(ws + L.off_key_slot_base);
     p.partial = (float*)(ws + off_delta + 2 * align_up(sizeof(float) * (size_t)d.hq * d.n_q, 256));
+    p.sched.prefix = (const long long*)(ws + L.off_fwd_prefix);
+    p.sched.order = p.fwd_order;
+    p.sched.n_tiles = L.n_fwd_tiles; p.sched.hkv = d.hkv; p.sched.G = d.hq / d.hkv; p.sched.n_gangs = L.row_gangs;
+    p.sched.w_first = kRowShareFirst; p.sched.w_second = kRowShareSecond;
+    p.row_partial = (float*)((char*)p.partial + dkv_partial_bytes(d, L));
     p.n_q = d.n_q; p.t_kv = d.t_kv; p.hq = d.hq; p.hkv = d.hkv;
     p.n_groups = L.n_groups; p.n_tiles = L.n_fwd_tiles; p.n_key_tiles = L.n_key_tiles;
     p.scale = d.scale;
@@ -728,7 +822,7 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
 
     const size_t n_lanes = (size_t)d.n_q * d.hq * (d.head_dim / 8);
     const unsigned grid_delta = (unsigned)((n_lanes + 255) / 256);
-    const unsigned grid_dq = (unsigned)((L.n_fwd_tiles + 7) / 8) * 8u * (unsigned)d.hq;
+    const unsigned grid_dq = (unsigned)L.row_gangs * (unsigned)(d.hq / d.hkv);
     const unsigned grid_dkv = (unsigned)L.dkv_max_items;         // items past the actual count exit at once
     const unsigned grid_fix = (unsigned)(L.n_key_tiles * d.hkv);
     const bool do_delta = !(d.flags & WLB_ATTN_BWD_SKIP_DELTA);
@@ -748,13 +842,19 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
             dkv_kernel<128><<<grid_dkv, 512, 0, stream>>>(p);
             dkv_fixup_kernel<128><<<grid_fix, 256, 0, stream>>>(p);
         }
-        if (do_dq) dq_kernel<128><<<grid_dq, 256, 0, dq_stream>>>(p);
+        if (do_dq) {
+            dq_kernel<128><<<grid_dq, 256, 0, dq_stream>>>(p);
+            dq_merge_kernel<128><<<grid_dq, 256, 0, dq_stream>>>(p);
+        }
     } else {
         if (do_dkv) {
             dkv_kernel<64><<<grid_dkv, 512, 0, stream>>>(p);
             dkv_fixup_kernel<64><<<grid_fix, 256, 0, stream>>>(p);
         }
-        if (do_dq) dq_kernel<64><<<grid_dq, 256, 0, dq_stream>>>(p);
+        if (do_dq) {
+            dq_kernel<64><<<grid_dq, 256, 0, dq_stream>>>(p);
+            dq_merge_kernel<64><<<grid_dq, 256, 0, dq_stream>>>(p);
+        }
     }
     if (side) {
         if (hipEventRecord(side->join, side->stream) != hipSuccess || hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
