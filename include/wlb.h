@@ -195,7 +195,11 @@ enum {
      * from and joined to the caller's stream with events), so that the dQ and dK/dV kernels fill
      * each other's idle compute units.  With this flag everything runs on the caller's stream, one
      * kernel after the other: each kernel's duration is then its own (profiling). */
-    WLB_ATTN_BWD_NO_OVERLAP = 16
+    WLB_ATTN_BWD_NO_OVERLAP = 16,
+    /* The forward and dQ kernels have two work schedules (see wlb_plan_layout: row_gangs); the
+     * library picks one from the shape.  These flags force one of them (tests, measurements). */
+    WLB_ATTN_SCHEDULE_GANGS = 32,
+    WLB_ATTN_SCHEDULE_ITEMS = 64
 };
 
 /* Bytes of device workspace needed (256-byte aligned pointer expected).  The forward needs

@@ -26,6 +26,8 @@ ATTN_BWD_SKIP_DELTA = 2
 ATTN_BWD_SKIP_DQ = 4
 ATTN_BWD_SKIP_DKV = 8
 ATTN_BWD_NO_OVERLAP = 16
+ATTN_SCHEDULE_GANGS = 32
+ATTN_SCHEDULE_ITEMS = 64
 
 STATUS_NAMES = {0: "WLB_OK", 1: "WLB_ERR_INVALID_ARG", 2: "WLB_ERR_BUFFER_TOO_SMALL",
                 3: "WLB_ERR_UNSUPPORTED", 4: "WLB_ERR_HIP"}
@@ -330,15 +332,17 @@ class Attention:
         wlb_attn_plan(self.desc, self.q_idx, self.cu_k, self.workspace)
         self.planned = True
 
-    def forward(self, q, k, v, o=None, lse=None):
+    def forward(self, q, k, v, o=None, lse=None, extra_flags=0):
         torch = self.torch
         n_q, _, _, hq, _, d, _ = self.shape
         if o is None:
             o = torch.empty((n_q, hq, d), dtype=torch.bfloat16, device=self.device)
         if lse is None:
             lse = torch.empty((hq, n_q), dtype=torch.float32, device=self.device)
-        wlb_attn_fwd(self.desc_reuse if self.planned else self.desc, q, k, v, self.q_idx, self.cu_k, o, lse,
-                     self.workspace)
+        desc = self.desc_reuse if self.planned else self.desc
+        if extra_flags:
+            desc = _desc(*self.shape, flags=desc.flags | extra_flags)
+        wlb_attn_fwd(desc, q, k, v, self.q_idx, self.cu_k, o, lse, self.workspace)
         self.planned = True
         return o, lse
 

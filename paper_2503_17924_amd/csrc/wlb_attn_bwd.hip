@@ -312,6 +312,24 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
     while (walk.next(p.sched, pc)) dq_piece<D>(p, smem, pc);
 }
 
+// The other schedule: one workgroup per (query tile in order, query head), heaviest first.
+template <int D>
+__global__ void __launch_bounds__(256, 2) dq_items_kernel(const BwdParams p) {
+    __shared__ __attribute__((aligned(1024))) char smem[4 * 64 * D * 2];
+    const int G = p.hq / p.hkv;
+    const int x = blockIdx.x & 7;
+    int y = blockIdx.x >> 3;
+    RowPiece pc;
+    pc.member = y % G; y /= G;
+    pc.hk = y % p.hkv;
+    const int rank = (y / p.hkv) * 8 + x;
+    if (rank >= p.n_tiles) return;
+    pc.tile = ld_const(p.sched.order + rank);
+    pc.c = (int)(ld_const64(p.sched.prefix + rank + 1) - ld_const64(p.sched.prefix + rank));
+    pc.a = 0; pc.b = pc.c; pc.slot = -1;
+    dq_piece<D>(p, smem, pc);
+}
+
 // Sums the partial dQ of a query tile that was cut at gang boundaries.  One workgroup per
 // (gang, member): it acts if its gang's last piece is the first part of a tile, and then takes
 // that part and the first piece of every later gang whose (non-empty) share begins inside the tile.
@@ -823,6 +841,8 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     const size_t n_lanes = (size_t)d.n_q * d.hq * (d.head_dim / 8);
     const unsigned grid_delta = (unsigned)((n_lanes + 255) / 256);
     const unsigned grid_dq = (unsigned)L.row_gangs * (unsigned)(d.hq / d.hkv);
+    const unsigned grid_dq_items = (unsigned)((L.n_fwd_tiles + 7) / 8) * 8u * (unsigned)d.hq;
+    const bool gangs = use_row_gangs(d, L);
     const unsigned grid_dkv = (unsigned)L.dkv_max_items;         // items past the actual count exit at once
     const unsigned grid_fix = (unsigned)(L.n_key_tiles * d.hkv);
     const bool do_delta = !(d.flags & WLB_ATTN_BWD_SKIP_DELTA);
@@ -842,18 +862,22 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
             dkv_kernel<128><<<grid_dkv, 512, 0, stream>>>(p);
             dkv_fixup_kernel<128><<<grid_fix, 256, 0, stream>>>(p);
         }
-        if (do_dq) {
+        if (do_dq && gangs) {
             dq_kernel<128><<<grid_dq, 256, 0, dq_stream>>>(p);
             dq_merge_kernel<128><<<grid_dq, 256, 0, dq_stream>>>(p);
+        } else if (do_dq) {
+            dq_items_kernel<128><<<grid_dq_items, 256, 0, dq_stream>>>(p);
         }
     } else {
         if (do_dkv) {
             dkv_kernel<64><<<grid_dkv, 512, 0, stream>>>(p);
             dkv_fixup_kernel<64><<<grid_fix, 256, 0, stream>>>(p);
         }
-        if (do_dq) {
+        if (do_dq && gangs) {
             dq_kernel<64><<<grid_dq, 256, 0, dq_stream>>>(p);
             dq_merge_kernel<64><<<grid_dq, 256, 0, dq_stream>>>(p);
+        } else if (do_dq) {
+            dq_items_kernel<64><<<grid_dq_items, 256, 0, dq_stream>>>(p);
         }
     }
     if (side) {

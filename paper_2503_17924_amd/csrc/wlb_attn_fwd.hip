@@ -323,6 +323,27 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
     while (walk.next(p.sched, pc)) fwd_piece<D>(p, smem, pc);
 }
 
+// The other schedule: one workgroup per (query tile in order, query head), dispatched heaviest
+// first.  With many tiles per workgroup slot the hardware's dynamic dispatch balances the load by
+// itself and adapts to whatever makes workgroups differ in speed; the gangs' fixed shares win when
+// there are only a few tiles per slot (long documents spread over many context-parallel ranks).
+template <int D>
+__global__ void __launch_bounds__(256, 2) fwd_items_kernel(const FwdParams p) {
+    __shared__ __attribute__((aligned(1024))) char smem[4 * 64 * D * 2];
+    const int G = p.hq / p.hkv;
+    const int x = blockIdx.x & 7;
+    int y = blockIdx.x >> 3;
+    RowPiece pc;
+    pc.member = y % G; y /= G;
+    pc.hk = y % p.hkv;
+    const int rank = (y / p.hkv) * 8 + x;
+    if (rank >= p.n_tiles) return;
+    pc.tile = ld_const(p.sched.order + rank);
+    pc.c = (int)(ld_const64(p.sched.prefix + rank + 1) - ld_const64(p.sched.prefix + rank));
+    pc.a = 0; pc.b = pc.c; pc.slot = -1;
+    fwd_piece<D>(p, smem, pc);
+}
+
 // Combines the partial results of a query tile that was cut at gang boundaries.  One workgroup per
 // (gang, member): it acts if its gang's last piece is the first part of a tile, and then takes
 // that part and the following gangs' first pieces.  With reference exponents e_i (log2 units), row
@@ -401,13 +422,19 @@ wlb_status launch_fwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.n_groups = L.n_groups; p.n_tiles = L.n_fwd_tiles;
     p.scale = d.scale;
     p.scale_log2e = d.scale * 1.4426950408889634f;
-    const unsigned grid = (unsigned)L.row_gangs * (unsigned)(d.hq / d.hkv);
-    if (d.head_dim == 128) {
-        fwd_kernel<128><<<grid, 256, 0, stream>>>(p);
-        fwd_merge_kernel<128><<<grid, 256, 0, stream>>>(p);
+    if (use_row_gangs(d, L)) {
+        const unsigned grid = (unsigned)L.row_gangs * (unsigned)(d.hq / d.hkv);
+        if (d.head_dim == 128) {
+            fwd_kernel<128><<<grid, 256, 0, stream>>>(p);
+            fwd_merge_kernel<128><<<grid, 256, 0, stream>>>(p);
+        } else {
+            fwd_kernel<64><<<grid, 256, 0, stream>>>(p);
+            fwd_merge_kernel<64><<<grid, 256, 0, stream>>>(p);
+        }
     } else {
-        fwd_kernel<64><<<grid, 256, 0, stream>>>(p);
-        fwd_merge_kernel<64><<<grid, 256, 0, stream>>>(p);
+        const unsigned grid = (unsigned)((L.n_fwd_tiles + 7) / 8) * 8u * (unsigned)d.hq;
+        if (d.head_dim == 128) fwd_items_kernel<128><<<grid, 256, 0, stream>>>(p);
+        else fwd_items_kernel<64><<<grid, 256, 0, stream>>>(p);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(WLB_ERR_HIP, "forward launch: %s", hipGetErrorString(e));

@@ -23,6 +23,8 @@ wlb_status check_desc(const wlb_attn_desc* d) {
         return fail(WLB_ERR_INVALID_ARG, "attention: n_q=%d t_kv=%d n_docs=%d hq=%d hkv=%d", d->n_q, d->t_kv,
                     d->n_docs, d->hq, d->hkv);
     if (d->hq % d->hkv != 0) return fail(WLB_ERR_INVALID_ARG, "attention: hq=%d not a multiple of hkv=%d", d->hq, d->hkv);
+    if ((d->flags & WLB_ATTN_SCHEDULE_GANGS) && (d->flags & WLB_ATTN_SCHEDULE_ITEMS))
+        return fail(WLB_ERR_INVALID_ARG, "attention: both schedule flags set");
     if (!(d->scale > 0.0f) || !std::isfinite(d->scale)) return fail(WLB_ERR_INVALID_ARG, "attention: scale must be finite and > 0");
     if (d->head_dim != 64 && d->head_dim != 128)
         return fail(WLB_ERR_UNSUPPORTED, "attention: head_dim=%d (64 and 128 are built)", d->head_dim);
@@ -30,7 +32,7 @@ wlb_status check_desc(const wlb_attn_desc* d) {
     // tensors are addressed through 32-bit buffer descriptors: each must stay under 4 GiB
     if (qe * 2 >= (1LL << 32) || ke * 2 >= (1LL << 32))
         return fail(WLB_ERR_UNSUPPORTED, "attention: a tensor of 4 GiB or more is not supported");
-    if (d->flags & ~(WLB_ATTN_REUSE_PLAN | WLB_ATTN_BWD_SKIP_DELTA | WLB_ATTN_BWD_SKIP_DQ | WLB_ATTN_BWD_SKIP_DKV | WLB_ATTN_BWD_NO_OVERLAP)) return fail(WLB_ERR_INVALID_ARG, "attention: unknown flag bits 0x%x", d->flags);
+    if (d->flags & ~(WLB_ATTN_REUSE_PLAN | WLB_ATTN_BWD_SKIP_DELTA | WLB_ATTN_BWD_SKIP_DQ | WLB_ATTN_BWD_SKIP_DKV | WLB_ATTN_BWD_NO_OVERLAP | WLB_ATTN_SCHEDULE_GANGS | WLB_ATTN_SCHEDULE_ITEMS)) return fail(WLB_ERR_INVALID_ARG, "attention: unknown flag bits 0x%x", d->flags);
     return WLB_OK;
 }
 
@@ -49,6 +51,13 @@ int compute_units() {
 size_t dkv_partial_bytes(const wlb_attn_desc& d, const wlb_plan_layout& L) {
     // one fp32 dK^T and dV^T tile per partial result
     return (size_t)L.dkv_max_partials * (2 * (size_t)kBwdKeyTile * d.head_dim * sizeof(float));
+}
+
+bool use_row_gangs(const wlb_attn_desc& d, const wlb_plan_layout& L) {
+    if (d.flags & WLB_ATTN_SCHEDULE_GANGS) return true;
+    if (d.flags & WLB_ATTN_SCHEDULE_ITEMS) return false;
+    const long long items = (long long)L.n_fwd_tiles * d.hq, slots = 2LL * compute_units();
+    return items < (long long)kRowGangMaxItemsPerSlot * slots;
 }
 
 size_t row_partial_bytes(const wlb_attn_desc& d, const wlb_plan_layout& L) {

@@ -49,19 +49,20 @@ class Case:
             self.bits["do"] = gather_rows(tens["do"], self.q_idx)
         self.dev = {n: B.bf16_bits_to_tensor(a, device) for n, a in self.bits.items()}
         self.attn = B.Attention(self.q_idx, self.cu_k, self.t_kv, hq, hkv, d, scale, device)
+        self.flags = 0          # extra descriptor flags for every call (e.g. a forced work schedule)
 
     def f64(self, name):
         return wl.bf16_bits_to_f64(self.bits[name])
 
     def run_fwd(self):
-        o, lse = self.attn.forward(self.dev["q"], self.dev["k"], self.dev["v"])
+        o, lse = self.attn.forward(self.dev["q"], self.dev["k"], self.dev["v"], extra_flags=self.flags)
         self.torch.cuda.synchronize()
         self.o, self.lse = o, lse
         return B.tensor_to_f64(o), B.tensor_to_f64(lse)
 
     def run_bwd(self):
         dq, dk, dv = self.attn.backward(self.dev["q"], self.dev["k"], self.dev["v"], self.o, self.lse,
-                                        self.dev["do"])
+                                        self.dev["do"], extra_flags=self.flags)
         self.torch.cuda.synchronize()
         return B.tensor_to_f64(dq), B.tensor_to_f64(dk), B.tensor_to_f64(dv)
 

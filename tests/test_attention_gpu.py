@@ -79,6 +79,21 @@ def test_forward_is_deterministic_and_plan_reuse_changes_nothing():
     assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
 
 
+@pytest.mark.parametrize("flag", [B.ATTN_SCHEDULE_GANGS, B.ATTN_SCHEDULE_ITEMS])
+def test_both_row_schedules_match_oracle(flag):
+    """Forward and dQ have two work schedules (fixed gangs with tiles cut at share ends and merged
+    from partial results / one workgroup per tile and head); both forced here on an input with
+    documents from 1 token to several tiles, pads, and tiles that straddle documents."""
+    docs = [900, 1, 37, 2600, 130, 64, 700]
+    w, tens = wl.small_case(77, docs, 4, 2, 128)
+    for cp, r in ((1, 0), (2, 1)):
+        sh = osh.shard(docs, cp, r, osh.PER_DOC_PADDED)
+        c = Case(tens, sh["q_idx"], sh["cu_seqlens_k"], 4, 2, 128, w.scale)
+        c.flags = flag
+        c.check_fwd(f" cp {cp} rank {r}")
+        c.check_bwd(f" cp {cp} rank {r}")
+
+
 ROW_ITEM_OVERHEAD = 6     # units of fixed cost per query tile in the forward / dQ work line
 
 
