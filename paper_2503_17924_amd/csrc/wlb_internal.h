@@ -40,9 +40,11 @@ constexpr int kRowItemOverhead = 6;
 #endif
 constexpr int kRowShareFirst = WLB_ROW_SHARE_FIRST, kRowShareSecond = 100 - WLB_ROW_SHARE_FIRST;
 // Which of the two forward / dQ schedules a launch uses: gangs with fixed shares when there are fewer
-// than kRowGangMaxItemsPerSlot (query tile, head) items per workgroup slot, else one workgroup per
-// item.  The WLB_ATTN_SCHEDULE_* flags override.
+// than kRowGangMaxItemsPerSlot (query tile, head) items per workgroup slot and an estimated
+// kRowGangMinUnitsPerSlot key tiles of work per slot, else one workgroup per item.  The
+// WLB_ATTN_SCHEDULE_* flags override.
 constexpr int kRowGangMaxItemsPerSlot = 3;
+constexpr int kRowGangMinUnitsPerSlot = 64;
 bool use_row_gangs(const wlb_attn_desc& d, const wlb_plan_layout& L);
 // floats of one partial result of a query tile and head: 128 x D accumulator, then 128 row sums and
 // 128 reference exponents

@@ -57,7 +57,11 @@ bool use_row_gangs(const wlb_attn_desc& d, const wlb_plan_layout& L) {
     if (d.flags & WLB_ATTN_SCHEDULE_GANGS) return true;
     if (d.flags & WLB_ATTN_SCHEDULE_ITEMS) return false;
     const long long items = (long long)L.n_fwd_tiles * d.hq, slots = 2LL * compute_units();
-    return items < (long long)kRowGangMaxItemsPerSlot * slots;
+    if (items >= (long long)kRowGangMaxItemsPerSlot * slots) return false;
+    // and only when a slot's share is worth cutting tiles for: estimated from the mean document length
+    // (a tile sees about half its document: length / 128 key tiles), since the host does not see the mask
+    const long long per_item = d.t_kv / d.n_docs / (2 * 64) + kRowItemOverhead;
+    return items * per_item >= (long long)kRowGangMinUnitsPerSlot * slots;
 }
 
 size_t row_partial_bytes(const wlb_attn_desc& d, const wlb_plan_layout& L) {
