@@ -36,7 +36,7 @@ struct BwdParams {
     const float* lse; float* delta; float* lse2;
     __bf16* dq; __bf16* dk; __bf16* dv;
     const int32_t* row_lo; const int32_t* row_hi; const int32_t* group; const int32_t* group_real;
-    const int32_t* fwd_order; const int32_t* key_order; const int32_t* key_range;
+    const int32_t* key_order; const int32_t* key_range;
     const int32_t* key_ways; const int32_t* key_item_base; const int32_t* key_slot_base;
     float* partial;
     RowSched sched;            // dQ: which query tiles, heads and key ranges a workgroup works on
@@ -91,12 +91,12 @@ __device__ __forceinline__ void dq_piece(const BwdParams& p, char* smem, const R
     const int l32 = lane & 31, half = lane >> 5;
     const int j16 = lane & 15, gi = (lane >> 4) & 1;
 
-    int k_lo = kPadLo, k_hi = 0, max_lo = 0, min_hi = kPadLo;
+    int k_lo = kPadLo, k_hi = 0;       // hull of the keys the tile's rows see
     for (int j = 0; j < BM / kGroupRows; ++j) {
         const int g = tile * (BM / kGroupRows) + j;
         if (g < p.n_groups) {
             const int4 d = reinterpret_cast<const int4*>(p.group)[g];
-            if (d.y > d.x) { k_lo = min(k_lo, d.x); k_hi = max(k_hi, d.y); max_lo = max(max_lo, d.z); min_hi = min(min_hi, d.w); }
+            if (d.y > d.x) { k_lo = min(k_lo, d.x); k_hi = max(k_hi, d.y); }
         }
     }
     int jb = 0, je = 0, fb = 0, fe = 0;
@@ -821,7 +821,6 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.row_hi = (const int32_t*)(ws + L.off_row_hi);
     p.group = (const int32_t*)(ws + L.off_group);
     p.group_real = (const int32_t*)(ws + L.off_group_real);
-    p.fwd_order = (const int32_t*)(ws + L.off_fwd_order);
     p.key_order = (const int32_t*)(ws + L.off_key_order);
     p.key_range = (const int32_t*)(ws + L.off_key_range);
     p.key_ways = (const int32_t*)(ws + L.off_key_ways);
@@ -829,7 +828,7 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.key_slot_base = (const int32_t*)(ws + L.off_key_slot_base);
     p.partial = (float*)(ws + off_delta + 2 * align_up(sizeof(float) * (size_t)d.hq * d.n_q, 256));
     p.sched.prefix = (const long long*)(ws + L.off_fwd_prefix);
-    p.sched.order = p.fwd_order;
+    p.sched.order = (const int32_t*)(ws + L.off_fwd_order);
     p.sched.n_tiles = L.n_fwd_tiles; p.sched.hkv = d.hkv; p.sched.G = d.hq / d.hkv; p.sched.n_gangs = L.row_gangs;
     p.sched.w_first = kRowShareFirst; p.sched.w_second = kRowShareSecond;
     p.row_partial = (float*)((char*)p.partial + dkv_partial_bytes(d, L));

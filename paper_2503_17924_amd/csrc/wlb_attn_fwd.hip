@@ -47,12 +47,12 @@ __device__ __forceinline__ void fwd_piece(const FwdParams& p, char* smem, const 
     const int l32 = lane & 31, half = lane >> 5;
     const int j16 = lane & 15, gi = (lane >> 4) & 1;
 
-    int k_lo = kPadLo, k_hi = 0, max_lo = 0, min_hi = kPadLo;
+    int k_lo = kPadLo, k_hi = 0;       // hull of the keys the tile's rows see
     for (int j = 0; j < BM / kGroupRows; ++j) {
         const int g = tile * (BM / kGroupRows) + j;
         if (g < p.n_groups) {
             const int4 d = reinterpret_cast<const int4*>(p.group)[g];
-            if (d.y > d.x) { k_lo = min(k_lo, d.x); k_hi = max(k_hi, d.y); max_lo = max(max_lo, d.z); min_hi = min(min_hi, d.w); }
+            if (d.y > d.x) { k_lo = min(k_lo, d.x); k_hi = max(k_hi, d.y); }
         }
     }
     int jb = 0, je = 0, fb = 0, fe = 0;

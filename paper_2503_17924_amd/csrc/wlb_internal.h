@@ -19,7 +19,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 constexpr int kLists = 8;         // XCDs: workgroup b runs on XCD b % 8
 #ifndef WLB_DKV_SPLIT
-#define WLB_DKV_SPLIT 8
+#define WLB_DKV_SPLIT 6
 #endif
 constexpr int kDkvSplit = WLB_DKV_SPLIT;      // a dK/dV item is at most 1/kDkvSplit of the mean load of a compute unit
 
