@@ -28,9 +28,9 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 COST_A, COST_B = 6, 640000    # packer cost model, picoseconds per token^2 / per token
 # HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size), measured with
 # rocprofv3 --pmc on this workload: profiles/hbm_traffic_c2_128k_cp8.txt
-MEASURED_TRAFFIC_BYTES = {("c2_128k_cp8", "dkv_kernel"): int((8.651 + 0.451) * 2**30),
+MEASURED_TRAFFIC_BYTES = {("c2_128k_cp8", "dkv_kernel"): int((4.018 + 0.246) * 2**30),
                           ("c2_128k_cp8", "dq_kernel"): int((3.009 + 0.077) * 2**30),
-                          ("c2_128k_cp8", "fwd_kernel"): int((2.953 + 0.078) * 2**30)}
+                          ("c2_128k_cp8", "fwd_kernel"): int((2.955 + 0.078) * 2**30)}
 
 
 def parse():
@@ -41,9 +41,6 @@ def parse():
     ap.add_argument("--config", type=int, default=2, help="workload index (2 = the 128K CP=8 config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-seq", action="store_true", help="skip the per-sequence sharding comparison")
-    ap.add_argument("--no-overlap", action="store_true",
-                    help="run the backward's dQ and dK/dV kernels one after the other on one stream (for kernel traces: "
-                         "by default they overlap on two streams and each one's wall duration includes the other's share)")
     ap.add_argument("--tiny-tail", action="store_true",
                     help="measure the small-document (HBM-bound) regime instead: the 1..64-token documents of "
                          "config 4 as their own 32768-token sequence, CP=1 and CP=4, reported as GB/s")
@@ -183,8 +180,7 @@ def main():
             if record is not None:
                 e1.record()
             if w.backward:
-                st.attn.backward(st.q, full["k"], full["v"], st.o, st.lse, st.do, st.dq, st.dk, st.dv,
-                                 extra_flags=B.ATTN_BWD_NO_OVERLAP if args.no_overlap else 0)
+                st.attn.backward(st.q, full["k"], full["v"], st.o, st.lse, st.do, st.dq, st.dk, st.dv)
             if record is not None:
                 e2.record()
                 record.append((e0, e1, e2))
@@ -318,8 +314,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "tokens": w.total_tokens, "cp_ranks_emulated": w.cp, "hq": hq, "hkv": w.hkv,
                    "head_dim": D, "n_docs": int(len(w.doc_len)), "longest_doc": int(w.doc_len.max()),
-                   "sharding": "per_document_padded", "useful_pairs": int(pairs),
-                   "backward_overlap": not args.no_overlap},
+                   "sharding": "per_document_padded", "useful_pairs": int(pairs)},
         "pct_of_bf16_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "pct_of_measured_mfma_ceiling_random_operands": round(100.0 * value / ceiling["random"], 2),
         "per_rank_latency": per_rank,

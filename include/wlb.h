@@ -191,11 +191,6 @@ enum {
     WLB_ATTN_BWD_SKIP_DELTA = 2,
     WLB_ATTN_BWD_SKIP_DQ = 4,
     WLB_ATTN_BWD_SKIP_DKV = 8,
-    /* By default wlb_attn_bwd runs its dQ kernel on a second stream owned by the library (forked
-     * from and joined to the caller's stream with events), so that the dQ and dK/dV kernels fill
-     * each other's idle compute units.  With this flag everything runs on the caller's stream, one
-     * kernel after the other: each kernel's duration is then its own (profiling). */
-    WLB_ATTN_BWD_NO_OVERLAP = 16,
     /* The forward and dQ kernels have two work schedules (see wlb_plan_layout: row_gangs); the
      * library picks one from the shape.  These flags force one of them (tests, measurements). */
     WLB_ATTN_SCHEDULE_GANGS = 32,

@@ -25,7 +25,6 @@ ATTN_REUSE_PLAN = 1
 ATTN_BWD_SKIP_DELTA = 2
 ATTN_BWD_SKIP_DQ = 4
 ATTN_BWD_SKIP_DKV = 8
-ATTN_BWD_NO_OVERLAP = 16
 ATTN_SCHEDULE_GANGS = 32
 ATTN_SCHEDULE_ITEMS = 64
 

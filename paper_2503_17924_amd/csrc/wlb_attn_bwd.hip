@@ -24,7 +24,6 @@
 #include <hip/hip_runtime.h>
 
 #include "wlb_device.h"
-#include <mutex>
 #include <type_traits>
 
 #include "wlb_internal.h"
@@ -786,27 +785,10 @@ __global__ void __launch_bounds__(256) dkv_fixup_kernel(const BwdParams p) {
     }
 }
 
-// dQ and dK/dV are independent once delta is known: the dQ kernel runs on a second stream of the
-// library's own (default priority, created once per device) so that the workgroups of one kernel
-// fill the compute units the other leaves idle towards its end.  Forked from and joined back to the
-// caller's stream with events, so the call stays asynchronous and ordered on the caller's stream.
-struct SideStream { hipStream_t stream = nullptr; hipEvent_t fork = nullptr, join = nullptr; bool ok = false; };
-static SideStream* side_stream() {
-    static SideStream per_device[64];
-    static std::mutex mu;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-    std::lock_guard<std::mutex> lock(mu);
-    SideStream& s = per_device[dev];
-    if (!s.ok) {
-        if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
-        if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
-        if (hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess) return nullptr;
-        s.ok = true;
-    }
-    return &s;
-}
-
+// delta, then dK/dV (+ fix-up), then dQ (+ merge), all on the caller's stream.  Running dQ beside
+// dK/dV on a second stream was measured: once each kernel keeps every compute unit busy to its end
+// the two only get in each other's way (their workgroups cannot share a compute unit's LDS), and the
+// step was 4 % slower.
 wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const void* q, const void* k,
                       const void* v, const void* o, const float* lse, const void* d_o, void* dq,
                       void* dk, void* dv, char* ws, size_t off_delta, void* stream_) {
@@ -849,23 +831,16 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     const bool do_dkv = !(d.flags & WLB_ATTN_BWD_SKIP_DKV);
     if (d.head_dim == 128) { if (do_delta) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p); }
     else { if (do_delta) delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p); }
-    hipStream_t dq_stream = stream;
-    SideStream* side = (do_dq && do_dkv && !(d.flags & WLB_ATTN_BWD_NO_OVERLAP)) ? side_stream() : nullptr;
-    if (side) {
-        if (hipEventRecord(side->fork, stream) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
-            return fail(WLB_ERR_HIP, "backward: fork to the second stream failed");
-        dq_stream = side->stream;
-    }
     if (d.head_dim == 128) {
         if (do_dkv) {
             dkv_kernel<128><<<grid_dkv, 512, 0, stream>>>(p);
             dkv_fixup_kernel<128><<<grid_fix, 256, 0, stream>>>(p);
         }
         if (do_dq && gangs) {
-            dq_kernel<128><<<grid_dq, 256, 0, dq_stream>>>(p);
-            dq_merge_kernel<128><<<grid_dq, 256, 0, dq_stream>>>(p);
+            dq_kernel<128><<<grid_dq, 256, 0, stream>>>(p);
+            dq_merge_kernel<128><<<grid_dq, 256, 0, stream>>>(p);
         } else if (do_dq) {
-            dq_items_kernel<128><<<grid_dq_items, 256, 0, dq_stream>>>(p);
+            dq_items_kernel<128><<<grid_dq_items, 256, 0, stream>>>(p);
         }
     } else {
         if (do_dkv) {
@@ -873,15 +848,11 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
             dkv_fixup_kernel<64><<<grid_fix, 256, 0, stream>>>(p);
         }
         if (do_dq && gangs) {
-            dq_kernel<64><<<grid_dq, 256, 0, dq_stream>>>(p);
-            dq_merge_kernel<64><<<grid_dq, 256, 0, dq_stream>>>(p);
+            dq_kernel<64><<<grid_dq, 256, 0, stream>>>(p);
+            dq_merge_kernel<64><<<grid_dq, 256, 0, stream>>>(p);
         } else if (do_dq) {
-            dq_items_kernel<64><<<grid_dq_items, 256, 0, dq_stream>>>(p);
+            dq_items_kernel<64><<<grid_dq_items, 256, 0, stream>>>(p);
         }
-    }
-    if (side) {
-        if (hipEventRecord(side->join, side->stream) != hipSuccess || hipStreamWaitEvent(stream, side->join, 0) != hipSuccess)
-            return fail(WLB_ERR_HIP, "backward: join from the second stream failed");
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(WLB_ERR_HIP, "backward launch: %s", hipGetErrorString(e));

@@ -32,7 +32,7 @@ wlb_status check_desc(const wlb_attn_desc* d) {
     // tensors are addressed through 32-bit buffer descriptors: each must stay under 4 GiB
     if (qe * 2 >= (1LL << 32) || ke * 2 >= (1LL << 32))
         return fail(WLB_ERR_UNSUPPORTED, "attention: a tensor of 4 GiB or more is not supported");
-    if (d->flags & ~(WLB_ATTN_REUSE_PLAN | WLB_ATTN_BWD_SKIP_DELTA | WLB_ATTN_BWD_SKIP_DQ | WLB_ATTN_BWD_SKIP_DKV | WLB_ATTN_BWD_NO_OVERLAP | WLB_ATTN_SCHEDULE_GANGS | WLB_ATTN_SCHEDULE_ITEMS)) return fail(WLB_ERR_INVALID_ARG, "attention: unknown flag bits 0x%x", d->flags);
+    if (d->flags & ~(WLB_ATTN_REUSE_PLAN | WLB_ATTN_BWD_SKIP_DELTA | WLB_ATTN_BWD_SKIP_DQ | WLB_ATTN_BWD_SKIP_DKV | WLB_ATTN_SCHEDULE_GANGS | WLB_ATTN_SCHEDULE_ITEMS)) return fail(WLB_ERR_INVALID_ARG, "attention: unknown flag bits 0x%x", d->flags);
     return WLB_OK;
 }
 
