@@ -79,19 +79,32 @@ def test_forward_is_deterministic_and_plan_reuse_changes_nothing():
     assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
 
 
+@pytest.mark.parametrize("hq,hkv,d", [(4, 2, 128), (6, 2, 64), (12, 1, 128), (3, 3, 64)])
 @pytest.mark.parametrize("flag", [B.ATTN_SCHEDULE_GANGS, B.ATTN_SCHEDULE_ITEMS])
-def test_both_row_schedules_match_oracle(flag):
+def test_both_row_schedules_match_oracle(flag, hq, hkv, d):
     """Forward and dQ have two work schedules (fixed gangs with tiles cut at share ends and merged
     from partial results / one workgroup per tile and head); both forced here on an input with
-    documents from 1 token to several tiles, pads, and tiles that straddle documents."""
+    documents from 1 token to several tiles, pads, and tiles that straddle documents, for head
+    groups of 1, 2, 3 and 12 query heads per KV head and both head dimensions."""
     docs = [900, 1, 37, 2600, 130, 64, 700]
-    w, tens = wl.small_case(77, docs, 4, 2, 128)
+    w, tens = wl.small_case(77, docs, hq, hkv, d)
     for cp, r in ((1, 0), (2, 1)):
         sh = osh.shard(docs, cp, r, osh.PER_DOC_PADDED)
-        c = Case(tens, sh["q_idx"], sh["cu_seqlens_k"], 4, 2, 128, w.scale)
+        c = Case(tens, sh["q_idx"], sh["cu_seqlens_k"], hq, hkv, d, w.scale)
         c.flags = flag
         c.check_fwd(f" cp {cp} rank {r}")
         c.check_bwd(f" cp {cp} rank {r}")
+
+
+def test_gang_schedule_on_one_row():
+    """Degenerate work lines: a single query row, and fewer units of work than gangs."""
+    for docs in ([1], [5, 1, 2]):
+        w, tens = wl.small_case(78, docs, 8, 1, 128)
+        sh = osh.shard(docs, 1, 0, osh.PER_DOC_PADDED)
+        c = Case(tens, sh["q_idx"], sh["cu_seqlens_k"], 8, 1, 128, w.scale)
+        c.flags = B.ATTN_SCHEDULE_GANGS
+        c.check_fwd(f" docs {docs}")
+        c.check_bwd(f" docs {docs}")
 
 
 ROW_ITEM_OVERHEAD = 6     # units of fixed cost per query tile in the forward / dQ work line
