@@ -199,17 +199,25 @@ __global__ void __launch_bounds__(256) plan_key_tiles_kernel(const int32_t* __re
     }
 }
 
-// order[rank] = index, heaviest first, ties by index (a counting rank; n is at most a few thousand)
-__global__ void plan_order_kernel(const int32_t* __restrict__ cost, int n, int32_t* __restrict__ order) {
+// order[rank] = index, heaviest first, ties by index (a counting rank; n is at most a few thousand).
+// The costs pass through LDS in chunks so that the n^2 comparisons do not each read global memory.
+__global__ void __launch_bounds__(256) plan_order_kernel(const int32_t* __restrict__ cost, int n, int32_t* __restrict__ order) {
+    constexpr int CHUNK = 2048;
+    __shared__ int s_cost[CHUNK];
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const int c = cost[i];
+    const int c = i < n ? cost[i] : 0;
     int rank = 0;
-    for (int j = 0; j < n; ++j) {
-        const int cj = cost[j];
-        rank += (cj > c) || (cj == c && j < i);
+    for (int j0 = 0; j0 < n; j0 += CHUNK) {
+        const int m = min(CHUNK, n - j0);
+        __syncthreads();
+        for (int j = threadIdx.x; j < m; j += blockDim.x) s_cost[j] = cost[j0 + j];
+        __syncthreads();
+        for (int j = 0; j < m; ++j) {
+            const int cj = s_cost[j];
+            rank += (cj > c) || (cj == c && j0 + j < i);
+        }
     }
-    order[rank] = i;
+    if (i < n) order[rank] = i;
 }
 
 // One workgroup.  Chooses how many items each key tile is split into and replaces the tile's
