@@ -275,6 +275,8 @@ def main():
                 "measured_mfma_ceiling_tflops": ceiling,
                 "frac_of_measured_ceiling_random_operands": round(tfl[dominant] / ceiling["random"], 4),
                 "traffic": traffic, "launch_ms": round(kern[dominant + "_ms"], 4),
+                "launch_ms_includes": {"dkv": "dkv_fixup_kernel (about 1 %)", "dq": "dq_merge_kernel (under 1 %)",
+                                       "fwd": "fwd_merge_kernel (under 2 %)"}[dominant],
                 "algorithmic_flops_per_launch": alg[dominant],
                 "per_kernel_tflops": {k: round(v, 2) for k, v in tfl.items()},
                 "per_kernel_ms_mean_over_ranks": {k: round(v, 4) for k, v in kern.items()}}
