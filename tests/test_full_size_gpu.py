@@ -159,12 +159,16 @@ def test_config4_tiny_document_tail(cp):
         c.check_bwd(f" cp {cp} rank {rank}")
 
 
-@pytest.mark.parametrize("cp", [1, 4])
-def test_config4_straggler_full(cp):
+@pytest.mark.parametrize("cp,flags", [(1, 0), (4, 0), (4, B.ATTN_SCHEDULE_GANGS)])
+def test_config4_straggler_full(cp, flags):
+    """flags = 0: the schedule the library picks for this shape (one workgroup per tile and head);
+    the gang schedule is forced once as well, so that tiles of a 98K-token document are cut and
+    merged at full size with 8 query heads per KV head."""
     w = wl.config(4)
     tens = w.tensors()
     sh = B.wlb_shard(w.doc_len, cp, cp - 1, B.SHARD_PER_DOC_PADDED)
     c = Case(tens, sh["q_idx"], sh["cu_seqlens_k"], w.hq, w.hkv, w.head_dim, w.scale)
+    c.flags = flags
     o, lse = c.run_fwd()
     dq, dk, dv = c.run_bwd()
     rng = np.random.default_rng(4)
