@@ -3,9 +3,10 @@
 // context-parallel rank's query rows against the whole packed sequence's K/V).
 //
 // A piece of work = one query tile of 128 local rows x one query head (or a part of its key
-// range), run by a workgroup of four wavefronts of 32 rows; the launch is a fixed set of
-// workgroups, each of which walks an equal share of all the work (see RowSched).  A wavefront keeps its bf16 Q operands, the running row max / sum and the transposed
-// output accumulator O^T[d][q] in registers.  Scores are computed transposed, S^T = K Q^T,
+// range), run by a workgroup of four wavefronts of 32 rows.  Two schedules hand out the pieces:
+// a fixed set of workgroups that each walk a share of all the work (RowSched in wlb_device.h),
+// or one workgroup per tile and head.  A wavefront keeps its bf16 Q operands, the running row
+// max / sum and the transposed output accumulator O^T[d][q] in registers.  Scores are computed transposed, S^T = K Q^T,
 // with the 32x32x16 bf16 MFMA: a lane then holds one query column and 16 key rows per block,
 // so the row max/sum are in-register reductions plus one exchange between the two lane
 // halves, and the exponentiated block is already laid out as the B operand of
