@@ -355,29 +355,13 @@ __global__ void __launch_bounds__(256) fwd_merge_kernel(const FwdParams p) {
     constexpr int BM = kFwdTileRows, PF = BM * D + 2 * BM, V4 = D / 4;
     const RowSched& s = p.sched;
     const int gang = (int)blockIdx.x / s.G, member = (int)blockIdx.x % s.G;
-    const long long W = s.hkv * ld_const64(s.prefix + s.n_tiles);
-    const long long w0 = s.share_begin(W, gang), w1 = s.share_begin(W, gang + 1);
-    if (w0 >= w1) return;
-    int r, hk;
-    RowWalk::locate(s, w1 - 1, r, hk);
-    const long long p0 = ld_const64(s.prefix + r);
-    const long long c = ld_const64(s.prefix + r + 1) - p0;
-    const long long st = s.hkv * p0 + hk * c;
-    if (st < w0 || w1 - st >= c) return;        // the gang's last piece is not the first part of a cut tile
-    // parts: this gang's last piece, then the first piece of every later gang whose (non-empty) share
-    // begins inside the tile
-    const long long tile_end = st + c;
-    const int tile = ld_const(s.order + r);
-    const int h = hk * s.G + member;
-    const float* first = p.partial + ((size_t)(2 * gang + 1) * s.G + member) * PF;
-    // calls f(part) for every later part
-    auto later_parts = [&](auto f) __attribute__((always_inline)) {
-        for (int g2 = gang + 1; g2 < s.n_gangs; ++g2) {
-            const long long b0 = s.share_begin(W, g2), b1 = s.share_begin(W, g2 + 1);
-            if (b0 >= tile_end) break;
-            if (b1 > b0) f(p.partial + ((size_t)(2 * g2) * s.G + member) * PF);
-        }
-    };
+    RowCut cut;
+    if (!cut.find(s, gang)) return;
+    const int tile = cut.tile;
+    const int h = cut.hk * s.G + member;
+    auto part = [&](int slot) { return p.partial + ((size_t)slot * s.G + member) * PF; };
+    const float* first = part(cut.first_slot());
+    auto later_parts = [&](auto f) __attribute__((always_inline)) { cut.later_parts([&](int slot) { f(part(slot)); }); };
     for (int e = threadIdx.x; e < BM * V4; e += 256) {
         const int rl = e / V4, d4 = e % V4;
         const int row = tile * BM + rl;

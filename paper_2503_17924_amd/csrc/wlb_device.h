@@ -157,6 +157,42 @@ struct RowWalk {
     }
 };
 
+// For the merge kernels: the query tile whose first part is gang `gang`'s last piece, if there is
+// one, and the partial results of its parts.  Partial slot 2g holds gang g's first piece when it
+// starts inside a tile, slot 2g + 1 its last piece when that ends inside a tile (times G members).
+struct RowCut {
+    const RowSched* s;
+    long long W, tile_end;
+    int gang, tile, hk;
+    // false: this gang's last piece is a whole tile or continues a tile begun by an earlier gang
+    __device__ __forceinline__ bool find(const RowSched& sched, int g) {
+        s = &sched; gang = g;
+        W = sched.hkv * ld_const64(sched.prefix + sched.n_tiles);
+        const long long w0 = sched.share_begin(W, g), w1 = sched.share_begin(W, g + 1);
+        if (w0 >= w1) return false;
+        int r;
+        RowWalk::locate(sched, w1 - 1, r, hk);
+        const long long p0 = ld_const64(sched.prefix + r);
+        const long long c = ld_const64(sched.prefix + r + 1) - p0;
+        const long long st = sched.hkv * p0 + hk * c;
+        if (st < w0 || w1 - st >= c) return false;
+        tile_end = st + c;
+        tile = ld_const(sched.order + r);
+        return true;
+    }
+    // slot index (before the member) of the first part
+    __device__ __forceinline__ int first_slot() const { return 2 * gang + 1; }
+    // calls f(slot index) for the first piece of every later gang whose (non-empty) share begins inside the tile
+    template <class F>
+    __device__ __forceinline__ void later_parts(F f) const {
+        for (int g2 = gang + 1; g2 < s->n_gangs; ++g2) {
+            const long long b0 = s->share_begin(W, g2), b1 = s->share_begin(W, g2 + 1);
+            if (b0 >= tile_end) break;
+            if (b1 > b0) f(2 * g2);
+        }
+    }
+};
+
 // XOR swizzle of the 16-byte chunks of an unpadded row-major LDS tile whose rows hold CPR
 // chunks: logical chunk cc of row r is stored at chunk swz(r, cc).  With 256-byte rows it
 // makes both access patterns of the kernels bank-conflict free: 16 rows x one chunk (b128
