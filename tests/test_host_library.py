@@ -247,3 +247,26 @@ def test_pack_optimal_node_limit_and_errors():
         B.wlb_pack_optimal(np.ones(65, dtype=np.int32), 2, 100, 1, 1)
     with pytest.raises(B.WlbError):
         B.wlb_pack_optimal([60, 60, 60], 2, 100, 1, 1)          # three documents of 60 cannot share two bins of 100
+
+
+def test_missing_library_is_an_error_not_a_fallback(tmp_path):
+    """With no built library every product call raises; nothing falls back to another implementation."""
+    import subprocess
+    import sys
+    code = (
+        "import numpy as np\n"
+        "from paper_2503_17924_amd import binding as B\n"
+        "for call in (lambda: B.wlb_pack(np.array([3, 2], dtype=np.int32), 2, 10, 1, 1),\n"
+        "             lambda: B.wlb_shard(np.array([8], dtype=np.int32), 2, 0, 0),\n"
+        "             lambda: B.wlb_attn_workspace_size(B._desc(8, 8, 1, 1, 1, 64, 1.0))):\n"
+        "    try:\n"
+        "        call()\n"
+        "    except RuntimeError as e:\n"
+        "        assert 'missing' in str(e)\n"
+        "    else:\n"
+        "        raise SystemExit('a call succeeded without the library')\n"
+        "print('ok')\n")
+    env = dict(os.environ, WLB_LIBRARY=str(tmp_path / "no_such_libwlb.so"))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env,
+                       cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    assert r.returncode == 0 and "ok" in r.stdout, r.stdout + r.stderr
