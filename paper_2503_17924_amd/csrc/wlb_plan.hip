@@ -161,9 +161,8 @@ __global__ void __launch_bounds__(256) plan_rows_kernel(const int32_t* __restric
 }
 
 // cost of a forward tile = number of 64-key tiles between the hull's ends
-__global__ void plan_fwd_cost_kernel(const int32_t* __restrict__ group, int n_groups, int n_tiles,
-                                     int groups_per_tile, int32_t* __restrict__ cost) {
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void fwd_cost_of_tile(const int32_t* __restrict__ group, int n_groups, int n_tiles,
+                                                 int groups_per_tile, int32_t* __restrict__ cost, int t) {
     if (t >= n_tiles) return;
     int k_lo = kPadLo, k_hi = 0;
     for (int j = 0; j < groups_per_tile; ++j) {
@@ -176,12 +175,10 @@ __global__ void plan_fwd_cost_kernel(const int32_t* __restrict__ group, int n_gr
 }
 
 // One wavefront per key tile: which groups have a hull that touches it.
-__global__ void __launch_bounds__(256) plan_key_tiles_kernel(const int32_t* __restrict__ group, int n_groups,
-                                                             int n_key_tiles, int key_tile, int t_kv,
-                                                             int32_t* __restrict__ key_range,
-                                                             int32_t* __restrict__ key_cost) {
+__device__ __forceinline__ void groups_of_key_tile(const int32_t* __restrict__ group, int n_groups, int n_key_tiles,
+                                                   int key_tile, int t_kv, int32_t* __restrict__ key_range,
+                                                   int32_t* __restrict__ key_cost, int kt) {
     const int lane = threadIdx.x & 63;
-    const int kt = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (kt >= n_key_tiles) return;
     const int k0 = kt * key_tile, k1 = min(k0 + key_tile, t_kv);
     int first = kPadLo, last = 0, cnt = 0;
@@ -199,12 +196,25 @@ __global__ void __launch_bounds__(256) plan_key_tiles_kernel(const int32_t* __re
     }
 }
 
+// Both read only the group table: the first fwd_blocks workgroups take the forward tiles (one per
+// thread), the others the key tiles (one per wavefront).
+__global__ void __launch_bounds__(256) plan_costs_kernel(const int32_t* __restrict__ group, int n_groups, int n_tiles,
+                                                         int groups_per_tile, int32_t* __restrict__ fwd_cost,
+                                                         int fwd_blocks, int n_key_tiles, int key_tile, int t_kv,
+                                                         int32_t* __restrict__ key_range, int32_t* __restrict__ key_cost) {
+    if ((int)blockIdx.x < fwd_blocks)
+        fwd_cost_of_tile(group, n_groups, n_tiles, groups_per_tile, fwd_cost, blockIdx.x * 256 + threadIdx.x);
+    else
+        groups_of_key_tile(group, n_groups, n_key_tiles, key_tile, t_kv, key_range, key_cost,
+                           ((int)blockIdx.x - fwd_blocks) * 4 + (threadIdx.x >> 6));
+}
+
 // order[rank] = index, heaviest first, ties by index (a counting rank; n is at most a few thousand).
 // The costs pass through LDS in chunks so that the n^2 comparisons do not each read global memory.
-__global__ void __launch_bounds__(256) plan_order_kernel(const int32_t* __restrict__ cost, int n, int32_t* __restrict__ order) {
+__device__ __forceinline__ void order_block(const int32_t* __restrict__ cost, int n, int32_t* __restrict__ order, int block) {
     constexpr int CHUNK = 2048;
     __shared__ int s_cost[CHUNK];
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int i = block * blockDim.x + threadIdx.x;
     const int c = i < n ? cost[i] : 0;
     int rank = 0;
     for (int j0 = 0; j0 < n; j0 += CHUNK) {
@@ -222,9 +232,8 @@ __global__ void __launch_bounds__(256) plan_order_kernel(const int32_t* __restri
 
 // One workgroup.  Chooses how many items each key tile is split into and replaces the tile's
 // cost by its item cost (groups in range x heads per item), the key the tiles are then ordered by.
-__global__ void __launch_bounds__(1024) plan_key_split_kernel(const int32_t* __restrict__ key_range, int n_key_tiles,
-                                                              int hq, int hkv, int n_slots, int32_t* __restrict__ ways,
-                                                              int32_t* __restrict__ item_cost) {
+__device__ __forceinline__ void key_split_block(const int32_t* __restrict__ key_range, int n_key_tiles, int hq, int hkv,
+                                                int n_slots, int32_t* __restrict__ ways, int32_t* __restrict__ item_cost) {
     __shared__ long long part[1024];
     long long sum = 0;
     for (int kt = threadIdx.x; kt < n_key_tiles; kt += 1024) sum += key_range[2 * kt + 1] - key_range[2 * kt];
@@ -283,9 +292,8 @@ __global__ void __launch_bounds__(1024) plan_key_bases_kernel(const int32_t* __r
 }
 
 // One workgroup.  prefix[r] = cost (key tiles + the fixed kRowItemOverhead each) of the query tiles of order rank < r.
-__global__ void __launch_bounds__(1024) plan_fwd_prefix_kernel(const int32_t* __restrict__ order,
-                                                               const int32_t* __restrict__ cost, int n_tiles,
-                                                               long long* __restrict__ prefix) {
+__device__ __forceinline__ void fwd_prefix_block(const int32_t* __restrict__ order, const int32_t* __restrict__ cost,
+                                                 int n_tiles, long long* __restrict__ prefix) {
     __shared__ long long s_sum[1024];
     const int per = (n_tiles + 1023) / 1024;
     const int r0 = min((int)threadIdx.x * per, n_tiles), r1 = min(r0 + per, n_tiles);
@@ -307,6 +315,30 @@ __global__ void __launch_bounds__(1024) plan_fwd_prefix_kernel(const int32_t* __
     if (threadIdx.x == 1023) prefix[n_tiles] = s_sum[1023];
 }
 
+// Workgroups [0, order_blocks) rank the forward tiles; the one after them splits the key tiles
+// (neither needs the other's result).
+__global__ void __launch_bounds__(1024) plan_fwd_order_key_split_kernel(const int32_t* __restrict__ fwd_cost, int n_tiles,
+                                                                        int32_t* __restrict__ fwd_order, int order_blocks,
+                                                                        const int32_t* __restrict__ key_range,
+                                                                        int n_key_tiles, int hq, int hkv, int n_slots,
+                                                                        int32_t* __restrict__ ways,
+                                                                        int32_t* __restrict__ item_cost) {
+    if ((int)blockIdx.x < order_blocks) order_block(fwd_cost, n_tiles, fwd_order, blockIdx.x);
+    else key_split_block(key_range, n_key_tiles, hq, hkv, n_slots, ways, item_cost);
+}
+
+// Workgroups [0, order_blocks) rank the key tiles by item cost; the one after them builds the
+// forward work line's prefix sums.
+__global__ void __launch_bounds__(1024) plan_key_order_fwd_prefix_kernel(const int32_t* __restrict__ key_cost,
+                                                                         int n_key_tiles, int32_t* __restrict__ key_order,
+                                                                         int order_blocks,
+                                                                         const int32_t* __restrict__ fwd_order,
+                                                                         const int32_t* __restrict__ fwd_cost, int n_tiles,
+                                                                         long long* __restrict__ prefix) {
+    if ((int)blockIdx.x < order_blocks) order_block(key_cost, n_key_tiles, key_order, blockIdx.x);
+    else fwd_prefix_block(fwd_order, fwd_cost, n_tiles, prefix);
+}
+
 wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const int32_t* q_idx,
                        const int32_t* cu_seqlens_k, char* ws, void* stream_) {
     hipStream_t stream = (hipStream_t)stream_;
@@ -321,15 +353,18 @@ wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const i
     int32_t* key_cost = (int32_t*)(ws + off_key_cost(L));
     plan_rows_kernel<<<(L.n_groups + 3) / 4, 256, 0, stream>>>(q_idx, cu_seqlens_k, d.n_q, d.t_kv, d.n_docs,
                                                                 L.n_groups, row_lo, row_hi, group, group_real);
-    plan_fwd_cost_kernel<<<(L.n_fwd_tiles + 255) / 256, 256, 0, stream>>>(group, L.n_groups, L.n_fwd_tiles,
-                                                                          kFwdTileRows / kGroupRows, fwd_cost);
-    plan_key_tiles_kernel<<<(L.n_key_tiles + 3) / 4, 256, 0, stream>>>(group, L.n_groups, L.n_key_tiles,
-                                                                       kBwdKeyTile, d.t_kv, key_range, key_cost);
-    plan_order_kernel<<<(L.n_fwd_tiles + 255) / 256, 256, 0, stream>>>(fwd_cost, L.n_fwd_tiles, fwd_order);
-    plan_fwd_prefix_kernel<<<1, 1024, 0, stream>>>(fwd_order, fwd_cost, L.n_fwd_tiles, (long long*)(ws + L.off_fwd_prefix));
     int32_t* key_ways = (int32_t*)(ws + L.off_key_ways);
-    plan_key_split_kernel<<<1, 1024, 0, stream>>>(key_range, L.n_key_tiles, d.hq, d.hkv, compute_units(), key_ways, key_cost);
-    plan_order_kernel<<<(L.n_key_tiles + 255) / 256, 256, 0, stream>>>(key_cost, L.n_key_tiles, key_order);
+    const int fwd_cost_blocks = (L.n_fwd_tiles + 255) / 256, key_tile_blocks = (L.n_key_tiles + 3) / 4;
+    plan_costs_kernel<<<fwd_cost_blocks + key_tile_blocks, 256, 0, stream>>>(
+        group, L.n_groups, L.n_fwd_tiles, kFwdTileRows / kGroupRows, fwd_cost, fwd_cost_blocks, L.n_key_tiles,
+        kBwdKeyTile, d.t_kv, key_range, key_cost);
+    const int fwd_order_blocks = (L.n_fwd_tiles + 1023) / 1024, key_order_blocks = (L.n_key_tiles + 1023) / 1024;
+    plan_fwd_order_key_split_kernel<<<fwd_order_blocks + 1, 1024, 0, stream>>>(
+        fwd_cost, L.n_fwd_tiles, fwd_order, fwd_order_blocks, key_range, L.n_key_tiles, d.hq, d.hkv, compute_units(),
+        key_ways, key_cost);
+    plan_key_order_fwd_prefix_kernel<<<key_order_blocks + 1, 1024, 0, stream>>>(
+        key_cost, L.n_key_tiles, key_order, key_order_blocks, fwd_order, fwd_cost, L.n_fwd_tiles,
+        (long long*)(ws + L.off_fwd_prefix));
     plan_key_bases_kernel<<<1, 1024, 0, stream>>>(key_order, key_ways, L.n_key_tiles, d.hkv,
                                                   (int32_t*)(ws + L.off_key_item_base), (int32_t*)(ws + L.off_key_slot_base));
     hipError_t e = hipGetLastError();

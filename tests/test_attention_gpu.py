@@ -263,3 +263,52 @@ def test_padding_free_sharding_forward_backward():
         c.check_fwd(f" rank {r}")
         c.check_bwd(f" rank {r}")
     assert sizes == {sum(docs) // cp}
+
+
+@pytest.mark.parametrize("flag", [0, B.ATTN_SCHEDULE_GANGS])
+def test_graph_replay_matches_eager_calls(flag):
+    """The library only launches kernels on the caller's stream, so schedule + forward + backward
+    can be captured into a HIP graph.  Every replay must reproduce the eager results bit for bit,
+    with eager calls and other inputs in between (the workspace is shared and rewritten)."""
+    import torch
+    c = _small(81, [700, 3, 260, 1, 90], 4, 2, 128)
+    other = _small(82, [700, 3, 260, 1, 90], 4, 2, 128)
+    a = c.attn
+    n_q = len(c.q_idx)
+    q, k, v, do = (c.dev[n].clone() for n in ("q", "k", "v", "do"))
+    o = torch.empty_like(q)
+    lse = torch.empty((c.hq, n_q), dtype=torch.float32, device=q.device)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+
+    def step():
+        a.plan()
+        a.forward(q, k, v, o, lse, extra_flags=flag)
+        a.backward(q, k, v, o, lse, do, dq, dk, dv, extra_flags=flag)
+
+    def results():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (o, lse, dq, dk, dv)]
+
+    step()
+    eager = results()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for replay in range(4):
+        for t in (o, lse, dq, dk, dv):
+            t.fill_(float("nan"))
+        if replay == 2:
+            # other inputs through the same graph, then back
+            for dst, name in ((q, "q"), (k, "k"), (v, "v"), (do, "do")):
+                dst.copy_(other.dev[name])
+            graph.replay()
+            step()
+            for dst, name in ((q, "q"), (k, "k"), (v, "v"), (do, "do")):
+                dst.copy_(c.dev[name])
+        graph.replay()
+        got = results()
+        for name, x, y in zip(("O", "LSE", "dQ", "dK", "dV"), got, eager):
+            assert torch.equal(x, y), f"{name} differs on replay {replay}"
+        step()                                        # eager work between the replays
+        for name, x, y in zip(("O", "LSE", "dQ", "dK", "dV"), results(), eager):
+            assert torch.equal(x, y), f"{name} differs in the eager call after replay {replay}"
