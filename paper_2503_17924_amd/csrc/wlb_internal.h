@@ -22,6 +22,10 @@ constexpr int kLists = 8;         // XCDs: workgroup b runs on XCD b % 8
 #define WLB_DKV_SPLIT 6
 #endif
 constexpr int kDkvSplit = WLB_DKV_SPLIT;      // a dK/dV item is at most 1/kDkvSplit of the mean load of a compute unit
+#ifndef WLB_DKV_MIN_ITEM_STAGES
+#define WLB_DKV_MIN_ITEM_STAGES 32
+#endif
+constexpr int kDkvMinItemStages = WLB_DKV_MIN_ITEM_STAGES;   // items this short are never split further
 
 // compute units of the GPU (256 when none is present: layout queries on the host)
 int compute_units();

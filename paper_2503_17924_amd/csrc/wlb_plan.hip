@@ -213,18 +213,21 @@ __global__ void __launch_bounds__(256) plan_costs_kernel(const int32_t* __restri
 // The costs pass through LDS in chunks so that the n^2 comparisons do not each read global memory.
 __device__ __forceinline__ void order_block(const int32_t* __restrict__ cost, int n, int32_t* __restrict__ order, int block) {
     constexpr int CHUNK = 2048;
-    __shared__ int s_cost[CHUNK];
+    __shared__ __attribute__((aligned(16))) int s_cost[CHUNK];
     const int i = block * blockDim.x + threadIdx.x;
     const int c = i < n ? cost[i] : 0;
     int rank = 0;
     for (int j0 = 0; j0 < n; j0 += CHUNK) {
         const int m = min(CHUNK, n - j0);
         __syncthreads();
-        for (int j = threadIdx.x; j < m; j += blockDim.x) s_cost[j] = cost[j0 + j];
+        // past the end: a cost below every real one (costs are >= 0), so it never counts
+        for (int j = threadIdx.x; j < CHUNK; j += blockDim.x) s_cost[j] = j < m ? cost[j0 + j] : -1;
         __syncthreads();
-        for (int j = 0; j < m; ++j) {
-            const int cj = s_cost[j];
-            rank += (cj > c) || (cj == c && j0 + j < i);
+        // entries before i win ties: compare (cost, -index) through c_before = c for j < i, c - 1 after
+        for (int j = 0; j < m; j += 4) {
+            const int4 cj = *reinterpret_cast<const int4*>(&s_cost[j]);
+            const int g = j0 + j;
+            rank += (cj.x > c - (g + 0 < i)) + (cj.y > c - (g + 1 < i)) + (cj.z > c - (g + 2 < i)) + (cj.w > c - (g + 3 < i));
         }
     }
     if (i < n) order[rank] = i;
@@ -245,7 +248,9 @@ __device__ __forceinline__ void key_split_block(const int32_t* __restrict__ key_
     }
     const int G = hq / hkv;
     const long long total_stages = part[0] * hq;
-    const long long thr = max(16LL, (total_stages + (long long)n_slots * kDkvSplit - 1) / ((long long)n_slots * kDkvSplit));
+    // An item of a few dozen stages is not worth splitting: its partial results and the fix-up pass
+    // cost more than the shorter tail saves (small-document inputs: 0.55 -> 0.48 ms with the minimum).
+    const long long thr = max((long long)kDkvMinItemStages, (total_stages + (long long)n_slots * kDkvSplit - 1) / ((long long)n_slots * kDkvSplit));
     for (int kt = threadIdx.x; kt < n_key_tiles; kt += 1024) {
         const int span = key_range[2 * kt + 1] - key_range[2 * kt];
         int w = 1;

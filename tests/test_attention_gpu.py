@@ -109,6 +109,7 @@ def test_gang_schedule_on_one_row():
 
 ROW_ITEM_OVERHEAD = 6     # units of fixed cost per query tile in the forward / dQ work line
 DKV_SPLIT = 6             # a dK/dV item is at most 1/DKV_SPLIT of a compute unit's mean load
+DKV_MIN_ITEM_STAGES = 32  # items this short are not split further
 
 
 def test_schedule_tables():
@@ -183,7 +184,7 @@ def test_schedule_tables():
         assert item_base[-1] <= lay.dkv_max_items and slot_base[-1] <= lay.dkv_max_partials
         # no item is heavier than the threshold unless it is already a single head
         total = int(span.sum()) * c.hq
-        assert (icost[ways < g_heads] <= max(16, -(-total // (DKV_SPLIT * n_cu)))).all()
+        assert (icost[ways < g_heads] <= max(DKV_MIN_ITEM_STAGES, -(-total // (DKV_SPLIT * n_cu)))).all()
 
 
 BWD_CASES = [
