@@ -210,12 +210,18 @@ __global__ void __launch_bounds__(256) plan_costs_kernel(const int32_t* __restri
 }
 
 // order[rank] = index, heaviest first, ties by index (a counting rank; n is at most a few thousand).
-// The costs pass through LDS in chunks so that the n^2 comparisons do not each read global memory.
+// A workgroup ranks kOrderPerBlock elements: wavefront w compares them with every (waves)th quad of
+// costs, which pass through LDS in chunks, and the partial ranks are summed in LDS.  (One element per
+// thread kept the n^2 comparisons on very few compute units: 40 us for 1024 key tiles.)
+constexpr int kOrderPerBlock = 64;
 __device__ __forceinline__ void order_block(const int32_t* __restrict__ cost, int n, int32_t* __restrict__ order, int block) {
     constexpr int CHUNK = 2048;
     __shared__ __attribute__((aligned(16))) int s_cost[CHUNK];
-    const int i = block * blockDim.x + threadIdx.x;
+    __shared__ int s_rank[kOrderPerBlock];
+    const int e = threadIdx.x % kOrderPerBlock, seg = threadIdx.x / kOrderPerBlock, n_seg = blockDim.x / kOrderPerBlock;
+    const int i = block * kOrderPerBlock + e;
     const int c = i < n ? cost[i] : 0;
+    if (threadIdx.x < kOrderPerBlock) s_rank[threadIdx.x] = 0;
     int rank = 0;
     for (int j0 = 0; j0 < n; j0 += CHUNK) {
         const int m = min(CHUNK, n - j0);
@@ -223,14 +229,16 @@ __device__ __forceinline__ void order_block(const int32_t* __restrict__ cost, in
         // past the end: a cost below every real one (costs are >= 0), so it never counts
         for (int j = threadIdx.x; j < CHUNK; j += blockDim.x) s_cost[j] = j < m ? cost[j0 + j] : -1;
         __syncthreads();
-        // entries before i win ties: compare (cost, -index) through c_before = c for j < i, c - 1 after
-        for (int j = 0; j < m; j += 4) {
+        // entries before i win ties: an entry counts if its cost exceeds c - 1 before i, c from i on
+        for (int j = 4 * seg; j < m; j += 4 * n_seg) {
             const int4 cj = *reinterpret_cast<const int4*>(&s_cost[j]);
             const int g = j0 + j;
             rank += (cj.x > c - (g + 0 < i)) + (cj.y > c - (g + 1 < i)) + (cj.z > c - (g + 2 < i)) + (cj.w > c - (g + 3 < i));
         }
     }
-    if (i < n) order[rank] = i;
+    atomicAdd(&s_rank[e], rank);
+    __syncthreads();
+    if (seg == 0 && i < n) order[s_rank[e]] = i;
 }
 
 // One workgroup.  Chooses how many items each key tile is split into and replaces the tile's
@@ -363,7 +371,8 @@ wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const i
     plan_costs_kernel<<<fwd_cost_blocks + key_tile_blocks, 256, 0, stream>>>(
         group, L.n_groups, L.n_fwd_tiles, kFwdTileRows / kGroupRows, fwd_cost, fwd_cost_blocks, L.n_key_tiles,
         kBwdKeyTile, d.t_kv, key_range, key_cost);
-    const int fwd_order_blocks = (L.n_fwd_tiles + 1023) / 1024, key_order_blocks = (L.n_key_tiles + 1023) / 1024;
+    const int fwd_order_blocks = (L.n_fwd_tiles + kOrderPerBlock - 1) / kOrderPerBlock;
+    const int key_order_blocks = (L.n_key_tiles + kOrderPerBlock - 1) / kOrderPerBlock;
     plan_fwd_order_key_split_kernel<<<fwd_order_blocks + 1, 1024, 0, stream>>>(
         fwd_cost, L.n_fwd_tiles, fwd_order, fwd_order_blocks, key_range, L.n_key_tiles, d.hq, d.hkv, compute_units(),
         key_ways, key_cost);
