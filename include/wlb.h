@@ -37,7 +37,7 @@ typedef enum {
     WLB_OK = 0,
     WLB_ERR_INVALID_ARG = 1,      /* null pointer, non-positive length, rank out of range, ... */
     WLB_ERR_BUFFER_TOO_SMALL = 2, /* workspace smaller than wlb_attn_workspace_size() asks for */
-    WLB_ERR_UNSUPPORTED = 3,      /* head_dim other than 64 or 128, sizes beyond the int32 range */
+    WLB_ERR_UNSUPPORTED = 3,      /* head_dim other than 64 or 128, sizes beyond the int32 range, a tensor near 4 GiB */
     WLB_ERR_HIP = 4               /* a HIP runtime call failed; text in wlb_last_error() */
 } wlb_status;
 
@@ -246,7 +246,8 @@ wlb_status wlb_attn_plan_layout(const wlb_attn_desc* desc, wlb_plan_layout* layo
 
 /* Forward.  Device pointers: q [n_q][hq][D], k, v [t_kv][hkv][D] (bf16), q_idx, cu_seqlens_k;
  * outputs o [n_q][hq][D] bf16 and lse [hq][n_q] float are overwritten.
- * Errors: INVALID_ARG (null pointer, bad desc), UNSUPPORTED (head_dim), BUFFER_TOO_SMALL,
+ * Errors: INVALID_ARG (null pointer, bad desc), UNSUPPORTED (head_dim; Q or K of 4 GiB or more,
+ * counting 128 rows past the end: the kernels address tensors with 32-bit offsets), BUFFER_TOO_SMALL,
  * HIP (launch failure).  Nothing is launched when an error is returned. */
 wlb_status wlb_attn_fwd(const wlb_attn_desc* desc, const void* q, const void* k, const void* v,
                         const int32_t* q_idx, const int32_t* cu_seqlens_k,

@@ -29,8 +29,10 @@ wlb_status check_desc(const wlb_attn_desc* d) {
     if (d->head_dim != 64 && d->head_dim != 128)
         return fail(WLB_ERR_UNSUPPORTED, "attention: head_dim=%d (64 and 128 are built)", d->head_dim);
     const int64_t qe = (int64_t)d->n_q * d->hq * d->head_dim, ke = (int64_t)d->t_kv * d->hkv * d->head_dim;
-    // tensors are addressed through 32-bit buffer descriptors: each must stay under 4 GiB
-    if (qe * 2 >= (1LL << 32) || ke * 2 >= (1LL << 32))
+    // tensors are addressed through 32-bit buffer descriptors: each must stay under 4 GiB, with
+    // room for the offsets of the rows a last, partly filled tile would have past the end
+    const int64_t q_margin = 2LL * kBwdKeyTile * d->hq * d->head_dim, k_margin = 2LL * kBwdKeyTile * d->hkv * d->head_dim;
+    if (qe * 2 + q_margin >= (1LL << 32) || ke * 2 + k_margin >= (1LL << 32))
         return fail(WLB_ERR_UNSUPPORTED, "attention: a tensor of 4 GiB or more is not supported");
     if (d->flags & ~(WLB_ATTN_REUSE_PLAN | WLB_ATTN_BWD_SKIP_DELTA | WLB_ATTN_BWD_SKIP_DQ | WLB_ATTN_BWD_SKIP_DKV | WLB_ATTN_SCHEDULE_GANGS | WLB_ATTN_SCHEDULE_ITEMS)) return fail(WLB_ERR_INVALID_ARG, "attention: unknown flag bits 0x%x", d->flags);
     return WLB_OK;

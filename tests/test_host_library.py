@@ -123,6 +123,15 @@ def test_attention_argument_checks_need_no_gpu():
     with pytest.raises(B.WlbError) as e:
         B.wlb_attn_workspace_size(d)
     assert e.value.status == 3
+    # tensors are addressed with 32-bit offsets: Q [n_q][hq][D] bf16 must stay under 4 GiB, tile tail included
+    for n_q, ok in ((131072 - 129, True), (131072 - 128, False), (131072, False)):
+        d = B._desc(n_q, 4096, 1, 128, 128, 128, 0.1)          # 32 KiB per row
+        if ok:
+            B.wlb_attn_workspace_size(d)
+        else:
+            with pytest.raises(B.WlbError) as e:
+                B.wlb_attn_workspace_size(d)
+            assert e.value.status == 3
     d = B._desc(1000, 4096, 5, 8, 2, 128, 0.1)
     f, b = B.wlb_attn_workspace_size(d)
     lay = B.wlb_attn_plan_layout(d)
