@@ -209,3 +209,45 @@ def test_config3_pack_then_attention():
     rows = _rows_sample(c.q_idx, c.cu_k, 16, np.random.default_rng(3))
     _check_rows(c, o, lse, dq, rows, "micro-batch")
     _check_identities(c, dq, dk, dv)
+
+
+def test_tensors_close_to_the_4gib_limit():
+    """Q, dO, O and dQ of 3.75 GiB each (122880 rows x 128 heads x 128): the kernels address tensors
+    with 32-bit offsets, so rows on both sides of the 2 GiB mark and at the very end are compared
+    with the oracle.  480 documents of 256 tokens keep the arithmetic small; each sampled document is
+    a self-contained problem (CP = 1), so the oracle runs on it alone."""
+    import torch
+    n_docs, doc, hq, hkv, d = 480, 256, 128, 16, 128
+    t = n_docs * doc
+    scale = 1.0 / float(np.sqrt(d))
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev).manual_seed(4096)
+    mk = lambda n, h: torch.randn((n, h, d), device=dev, generator=g, dtype=torch.float32).to(torch.bfloat16)
+    k, v = mk(t, hkv), mk(t, hkv)
+    q = torch.empty((t, hq, d), dtype=torch.bfloat16, device=dev)
+    do = torch.empty_like(q)
+    for r0 in range(0, t, 8192):                     # in pieces: no 7.5 GiB fp32 temporary
+        q[r0:r0 + 8192] = mk(min(8192, t - r0), hq)
+        do[r0:r0 + 8192] = mk(min(8192, t - r0), hq)
+    assert q.numel() * 2 > 3.7 * 2**30
+    cu = (np.arange(n_docs + 1) * doc).astype(np.int32)
+    attn = B.Attention(np.arange(t, dtype=np.int32), cu, t, hq, hkv, d, scale)
+    o, lse = attn.forward(q, k, v)
+    dq, dk, dv = attn.backward(q, k, v, o, lse, do)
+    torch.cuda.synchronize()
+    f64 = lambda x: x.double().cpu().numpy()
+    # 2 GiB / 32 KiB per row = row 65536 = first row of document 256
+    for i in (0, 255, 256, 300, n_docs - 1):
+        a, b = i * doc, (i + 1) * doc
+        qi, cui = np.arange(doc, dtype=np.int32), np.array([0, doc], dtype=np.int32)
+        args = (f64(q[a:b]), f64(k[a:b]), f64(v[a:b]))
+        ro, rlse = oat.attn_fwd(*args, qi, cui, scale)
+        check_close(f"O document {i}", f64(o[a:b]), ro)
+        assert np.abs(f64(lse[:, a:b]) - rlse).max() <= LSE_ABS
+        rdq, rdk, rdv = oat.attn_bwd(*args, f64(do[a:b]), qi, cui, scale)
+        check_close(f"dQ document {i}", f64(dq[a:b]), rdq)
+        check_close(f"dK document {i}", f64(dk[a:b]), rdk)
+        check_close(f"dV document {i}", f64(dv[a:b]), rdv)
+    # nothing anywhere is left unwritten or non-finite
+    for name, x in (("O", o), ("dQ", dq), ("dK", dk), ("dV", dv)):
+        assert bool(torch.isfinite(x.view(-1)[::257].float()).all()), name
