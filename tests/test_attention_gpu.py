@@ -187,6 +187,42 @@ def test_schedule_tables():
         assert (icost[ways < g_heads] <= max(DKV_MIN_ITEM_STAGES, -(-total // (DKV_SPLIT * n_cu)))).all()
 
 
+def test_schedule_orders_with_thousands_of_tiles():
+    """600K tokens: more tiles than one pass of the counting rank holds.  Both orders must be the
+    stable sort by cost, heaviest first (ties by index), and the running sums must follow them."""
+    import torch
+    rng = np.random.default_rng(5)
+    docs = [200000, 70001] + rng.integers(1, 3000, size=220).tolist()
+    cu = np.concatenate([[0], np.cumsum(docs)]).astype(np.int32)
+    t = int(cu[-1])
+    attn = B.Attention(np.arange(t, dtype=np.int32), cu, t, 2, 1, 64, 0.125)
+    attn.plan()
+    torch.cuda.synchronize()
+    lay = B.wlb_attn_plan_layout(attn.desc)
+    assert lay.n_fwd_tiles > 4096 and lay.n_key_tiles > 4096
+    ws = attn.workspace.cpu().numpy()
+    arr = lambda off, n: ws[off:off + 4 * n].view(np.int32)
+    cost = arr(lay.off_fwd_cost, lay.n_fwd_tiles)
+    # a query tile's cost: 64-key tiles from its first row's document start to its last row
+    tile_rows = t // lay.n_fwd_tiles + (t % lay.n_fwd_tiles > 0)
+    assert tile_rows == 128
+    first = np.arange(lay.n_fwd_tiles) * 128
+    last = np.minimum(first + 128, t) - 1
+    lo = cu[np.searchsorted(cu, first, side="right") - 1]
+    assert (cost == (last + 1 + 63) // 64 - lo // 64).all()
+    order = arr(lay.off_fwd_order, lay.n_fwd_tiles)
+    assert (order == np.lexsort((np.arange(lay.n_fwd_tiles), -cost))).all()
+    prefix = ws[lay.off_fwd_prefix:lay.off_fwd_prefix + 8 * (lay.n_fwd_tiles + 1)].view(np.int64)
+    assert prefix[0] == 0 and (np.diff(prefix) == cost[order].astype(np.int64) + ROW_ITEM_OVERHEAD).all()
+    krange = arr(lay.off_key_range, 2 * lay.n_key_tiles).reshape(-1, 2)
+    ways = arr(lay.off_key_ways, lay.n_key_tiles)
+    icost = (krange[:, 1] - krange[:, 0]) * (2 // ways)
+    korder = arr(lay.off_key_order, lay.n_key_tiles)
+    assert (korder == np.lexsort((np.arange(lay.n_key_tiles), -icost))).all()
+    item_base = arr(lay.off_key_item_base, lay.n_key_tiles + 1)
+    assert item_base[0] == 0 and (np.diff(item_base) == ways[korder]).all()
+
+
 BWD_CASES = [
     ([300, 45, 1, 700, 130], 4, 2, 128, 1),
     ([64, 64, 128], 2, 2, 64, 1),
