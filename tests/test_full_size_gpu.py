@@ -251,3 +251,25 @@ def test_tensors_close_to_the_4gib_limit():
     # nothing anywhere is left unwritten or non-finite
     for name, x in (("O", o), ("dQ", dq), ("dK", dk), ("dV", dv)):
         assert bool(torch.isfinite(x.view(-1)[::257].float()).all()), name
+
+
+@pytest.mark.parametrize("flags", [0, B.ATTN_SCHEDULE_GANGS])
+def test_half_million_token_document(flags):
+    """A 500000-token document (4x the benchmark's window), CP=4, rank 0 (first and last chunk of
+    every document): thousands of key tiles per query tile, work lines of millions of units."""
+    docs = [500000, 24288]
+    w, tens = wl.small_case(91, docs, 2, 1, 64)
+    sh = B.wlb_shard(np.asarray(docs, dtype=np.int32), 4, 0, B.SHARD_PER_DOC_PADDED)
+    c = Case(tens, sh["q_idx"], sh["cu_seqlens_k"], 2, 1, 64, w.scale)
+    c.flags = flags
+    o, lse = c.run_fwd()
+    dq, dk, dv = c.run_bwd()
+    rows = _rows_sample(c.q_idx, c.cu_k, 24, np.random.default_rng(9))
+    _check_rows(c, o, lse, dq, rows, "500K")
+    cu = c.cu_k
+    for d in range(2):
+        lo = cu[d + 1] - 512
+        tail = np.nonzero((c.q_idx >= lo) & (c.q_idx < cu[d + 1]))[0]
+        assert len(tail)
+        _check_dkv_for_rows(c, dk, dv, tail, lo, cu[d + 1], f"tail of document {d}")
+    _check_identities(c, dq, dk, dv)
