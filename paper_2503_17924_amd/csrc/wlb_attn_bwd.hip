@@ -7,7 +7,8 @@
 // parallelism (Section 2.1) dK/dV hold only the calling rank's rows' contribution.
 //
 // Five kernels, no atomics, deterministic:
-//   delta_kernel      delta[h][i] = sum_d dO*O and the log2-scaled LSE copy (0 / +inf for padding rows)
+//   delta_kernel      delta[h][i] = -sum_d dO*O (stored negated: the dK/dV kernel starts its dP
+//                     accumulators from it) and the log2-scaled LSE copy (0 / +inf for padding rows)
 //   dq_kernel         query-stationary, same tiling and work schedule as the forward: S^T and dP^T
 //                     per lane column, dQ^T += K^T dS^T with K^T read from LDS by transpose reads
 //   dq_merge_kernel   sums the fp32 partial dQ of query tiles cut at a gang boundary
@@ -64,7 +65,7 @@ __global__ void __launch_bounds__(256) delta_kernel(const BwdParams p) {
     if (rh < total && c == 0) {
         const int row = (int)(rh / p.hq), h = (int)(rh % p.hq);
         const bool real = p.row_hi[row] > 0;
-        p.delta[(size_t)h * p.n_q + row] = real ? acc : 0.f;
+        p.delta[(size_t)h * p.n_q + row] = real ? -acc : 0.f;
         // LSE in log2 units for the dK/dV kernel; +inf makes every probability of a padding row 0
         p.lse2[(size_t)h * p.n_q + row] = real ? p.lse[(size_t)h * p.n_q + row] * 1.4426950408889634f : INFINITY;
     }
@@ -205,7 +206,7 @@ __device__ __forceinline__ void dq_piece(const BwdParams& p, char* smem, const R
         // dS^T = P^T o (dP^T - delta), in place of s; ls = the row's LSE, or +inf to switch the lane off
         auto grads = [&](f32x16& s, const f32x16& dp, float ls) __attribute__((always_inline)) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], cs, -ls)) * (dp[r] - dl);
+            for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], cs, -ls)) * (dp[r] + dl);
         };
         // a block outside the fully visible range: rows that see none of its 32 keys (rows of another
         // document in the same wavefront) are switched off as whole lanes; the element-wise mask is
@@ -585,17 +586,26 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
         *reinterpret_cast<WLB_LDS bf16x8*>((uintptr_t)(paddr + (qb * 2 + cc) * 1024)) = pk;
         return pk;
     };
-    // dS of 16 rows: P (from the partner) x (dP - delta)
+    // dS of 16 rows: P (from the partner) x (dP - delta); the dP accumulators start from -delta
     auto load_p = [&](int qb, int cc) __attribute__((always_inline)) {
         return *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(paddr + (qb * 2 + cc) * 1024));
     };
-    auto ds_half = [&](const f32x16& dn, const bf16x8& pv, const RowVals& dl, int cc) __attribute__((always_inline)) {
+    auto ds_half = [&](const f32x16& dn, const bf16x8& pv, int cc) __attribute__((always_inline)) {
         float ds[8];
 #pragma unroll
         for (int r2 = 0; r2 < 2; ++r2)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) ds[r2 * 4 + i] = (float)pv[r2 * 4 + i] * (dn[(cc * 2 + r2) * 4 + i] - dl.v[r2][i]);
+            for (int i = 0; i < 4; ++i) ds[r2 * 4 + i] = (float)pv[r2 * 4 + i] * dn[(cc * 2 + r2) * 4 + i];
         return pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
+    };
+    // -delta of the 32 rows of block qb, in accumulator order
+    auto load_neg_delta = [&](f32x16& o, int qb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int g8 = 0; g8 < 4; ++g8) {
+            const f32x4 x = lds_f4(saddr + GR * 4 + (qb * 32 + g8 * 8) * 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[g8 * 4 + i] = x[i];
+        }
     };
     // The fences pin the order "request unit u+1, run unit u"; the exponentials / dS products of
     // one row block are placed beside the MFMAs of the units that do not depend on them.
@@ -627,28 +637,25 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
     };
     auto grad_stage = [&]() __attribute__((always_inline)) {
         f32x16 d0, d1;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { d0[r] = 0.f; d1[r] = 0.f; }
         RowOps ra, rb;
         ColOps ca, cb;
-        RowVals la, lb;
         bf16x8 pa, pb;
-        load_rows(ra, 0, 0);
-        load_rows(rb, 0, 1);                                               fence();  mfma_rows(d0, ra, 0);  fence();
-        load_rows(ra, 1, 0);  load_vals(la, 1, 0, 0);  pa = load_p(0, 0);  fence();  mfma_rows(d0, rb, 1);  fence();
-        load_rows(rb, 1, 1);  load_vals(lb, 1, 0, 1);  pb = load_p(0, 1);  fence();  mfma_rows(d1, ra, 0);
-        const bf16x8 e00 = ds_half(d0, pa, la, 0);
+        load_rows(ra, 0, 0);  load_neg_delta(d0, 0);
+        load_rows(rb, 0, 1);                           fence();  mfma_rows(d0, ra, 0);  fence();
+        load_rows(ra, 1, 0);  load_neg_delta(d1, 1);  pa = load_p(0, 0);  fence();  mfma_rows(d0, rb, 1);  fence();
+        load_rows(rb, 1, 1);  pb = load_p(0, 1);      fence();  mfma_rows(d1, ra, 0);
+        const bf16x8 e00 = ds_half(d0, pa, 0);
         fence();
-        load_cols(ca, 0);     load_vals(la, 1, 1, 0);  pa = load_p(1, 0);  fence();  mfma_rows(d1, rb, 1);
-        const bf16x8 e01 = ds_half(d0, pb, lb, 1);
+        load_cols(ca, 0);     pa = load_p(1, 0);      fence();  mfma_rows(d1, rb, 1);
+        const bf16x8 e01 = ds_half(d0, pb, 1);
         fence();
-        load_cols(cb, 1);     load_vals(lb, 1, 1, 1);  pb = load_p(1, 1);  fence();  mfma_cols(ca, e00);
-        const bf16x8 e10 = ds_half(d1, pa, la, 0);
+        load_cols(cb, 1);     pb = load_p(1, 1);      fence();  mfma_cols(ca, e00);
+        const bf16x8 e10 = ds_half(d1, pa, 0);
         fence();
-        load_cols(ca, 2);                                                  fence();  mfma_cols(cb, e01);
-        const bf16x8 e11 = ds_half(d1, pb, lb, 1);
+        load_cols(ca, 2);                             fence();  mfma_cols(cb, e01);
+        const bf16x8 e11 = ds_half(d1, pb, 1);
         fence();
-        load_cols(cb, 3);                                                  fence();  mfma_cols(ca, e10);  fence();
+        load_cols(cb, 3);                             fence();  mfma_cols(ca, e10);  fence();
         mfma_cols(cb, e11);
     };
 
