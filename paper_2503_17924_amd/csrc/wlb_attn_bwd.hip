@@ -337,14 +337,16 @@ template <int D>
 __global__ void __launch_bounds__(256) dq_merge_kernel(const BwdParams p) {
     constexpr int BM = kFwdTileRows, PF = BM * D + 2 * BM, V4 = D / 4;
     const RowSched& s = p.sched;
-    const int gang = (int)blockIdx.x / s.G, member = (int)blockIdx.x % s.G;
+    const int job = (int)blockIdx.x / kMergeSplit, quarter = (int)blockIdx.x % kMergeSplit;
+    const int gang = job / s.G, member = job % s.G;
     RowCut cut;
     if (!cut.find(s, gang)) return;
     const int tile = cut.tile;
     const int h = cut.hk * s.G + member;
     auto part = [&](int slot) { return p.row_partial + ((size_t)slot * s.G + member) * PF; };
     const float* first = part(cut.first_slot());
-    for (int e = threadIdx.x; e < BM * V4; e += 256) {
+    constexpr int PER = BM * V4 / kMergeSplit;
+    for (int e = quarter * PER + threadIdx.x; e < (quarter + 1) * PER; e += 256) {
         const int rl = e / V4, d4 = e % V4;
         const int row = tile * BM + rl;
         if (row >= p.n_q) continue;
@@ -760,14 +762,16 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
 template <int D>
 __global__ void __launch_bounds__(256) dkv_fixup_kernel(const BwdParams p) {
     constexpr int BNK = kBwdKeyTile;
-    const int hk = blockIdx.x % p.hkv, r = blockIdx.x / p.hkv;
+    const int job = (int)blockIdx.x / kMergeSplit, quarter = (int)blockIdx.x % kMergeSplit;
+    const int hk = job % p.hkv, r = job / p.hkv;
     const int kt = p.key_order[r];
     const int ways = p.key_ways[kt];
     if (ways == 1) return;                      // one item did the whole tile and wrote dK/dV itself
     const int k0 = kt * BNK, nk = min(BNK, p.t_kv - k0);
     const float* src = p.partial + (size_t)(p.key_slot_base[r] + hk * ways) * (2 * BNK * D);
     constexpr int V4 = D / 4;                   // float4 per row
-    for (int e = threadIdx.x; e < 2 * BNK * V4; e += 256) {
+    constexpr int PER = 2 * BNK * V4 / kMergeSplit;
+    for (int e = quarter * PER + threadIdx.x; e < (quarter + 1) * PER; e += 256) {
         const int which = e / (BNK * V4), rem = e % (BNK * V4);
         const int key = rem / V4, d4 = rem % V4;
         if (key >= nk) continue;
@@ -830,22 +834,22 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     if (d.head_dim == 128) {
         if (do_dkv) {
             dkv_kernel<128><<<grid_dkv, 512, 0, stream>>>(p);
-            dkv_fixup_kernel<128><<<grid_fix, 256, 0, stream>>>(p);
+            dkv_fixup_kernel<128><<<grid_fix * kMergeSplit, 256, 0, stream>>>(p);
         }
         if (do_dq && gangs) {
             dq_kernel<128><<<grid_dq, 256, 0, stream>>>(p);
-            dq_merge_kernel<128><<<grid_dq, 256, 0, stream>>>(p);
+            dq_merge_kernel<128><<<grid_dq * kMergeSplit, 256, 0, stream>>>(p);
         } else if (do_dq) {
             dq_items_kernel<128><<<grid_dq_items, 256, 0, stream>>>(p);
         }
     } else {
         if (do_dkv) {
             dkv_kernel<64><<<grid_dkv, 512, 0, stream>>>(p);
-            dkv_fixup_kernel<64><<<grid_fix, 256, 0, stream>>>(p);
+            dkv_fixup_kernel<64><<<grid_fix * kMergeSplit, 256, 0, stream>>>(p);
         }
         if (do_dq && gangs) {
             dq_kernel<64><<<grid_dq, 256, 0, stream>>>(p);
-            dq_merge_kernel<64><<<grid_dq, 256, 0, stream>>>(p);
+            dq_merge_kernel<64><<<grid_dq * kMergeSplit, 256, 0, stream>>>(p);
         } else if (do_dq) {
             dq_items_kernel<64><<<grid_dq_items, 256, 0, stream>>>(p);
         }

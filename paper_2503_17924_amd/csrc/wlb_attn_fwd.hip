@@ -354,7 +354,10 @@ template <int D>
 __global__ void __launch_bounds__(256) fwd_merge_kernel(const FwdParams p) {
     constexpr int BM = kFwdTileRows, PF = BM * D + 2 * BM, V4 = D / 4;
     const RowSched& s = p.sched;
-    const int gang = (int)blockIdx.x / s.G, member = (int)blockIdx.x % s.G;
+    // kMergeSplit workgroups share a tile's rows: the work is a few dependent loads per element, so
+    // the launch needs many wavefronts in flight rather than long loops
+    const int job = (int)blockIdx.x / kMergeSplit, quarter = (int)blockIdx.x % kMergeSplit;
+    const int gang = job / s.G, member = job % s.G;
     RowCut cut;
     if (!cut.find(s, gang)) return;
     const int tile = cut.tile;
@@ -362,7 +365,8 @@ __global__ void __launch_bounds__(256) fwd_merge_kernel(const FwdParams p) {
     auto part = [&](int slot) { return p.partial + ((size_t)slot * s.G + member) * PF; };
     const float* first = part(cut.first_slot());
     auto later_parts = [&](auto f) __attribute__((always_inline)) { cut.later_parts([&](int slot) { f(part(slot)); }); };
-    for (int e = threadIdx.x; e < BM * V4; e += 256) {
+    constexpr int PER = BM * V4 / kMergeSplit;
+    for (int e = quarter * PER + threadIdx.x; e < (quarter + 1) * PER; e += 256) {
         const int rl = e / V4, d4 = e % V4;
         const int row = tile * BM + rl;
         if (row >= p.n_q) continue;
@@ -411,10 +415,10 @@ wlb_status launch_fwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
         const unsigned grid = (unsigned)L.row_gangs * (unsigned)(d.hq / d.hkv);
         if (d.head_dim == 128) {
             fwd_kernel<128><<<grid, 256, 0, stream>>>(p);
-            fwd_merge_kernel<128><<<grid, 256, 0, stream>>>(p);
+            fwd_merge_kernel<128><<<grid * kMergeSplit, 256, 0, stream>>>(p);
         } else {
             fwd_kernel<64><<<grid, 256, 0, stream>>>(p);
-            fwd_merge_kernel<64><<<grid, 256, 0, stream>>>(p);
+            fwd_merge_kernel<64><<<grid * kMergeSplit, 256, 0, stream>>>(p);
         }
     } else {
         const unsigned grid = (unsigned)((L.n_fwd_tiles + 7) / 8) * 8u * (unsigned)d.hq;

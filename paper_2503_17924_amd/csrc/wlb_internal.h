@@ -26,6 +26,7 @@ constexpr int kDkvSplit = WLB_DKV_SPLIT;      // a dK/dV item is at most 1/kDkvS
 #define WLB_DKV_MIN_ITEM_STAGES 32
 #endif
 constexpr int kDkvMinItemStages = WLB_DKV_MIN_ITEM_STAGES;   // items this short are never split further
+constexpr int kMergeSplit = 4;     // workgroups per cut query tile and head in the merge kernels (rows split evenly)
 
 // compute units of the GPU (256 when none is present: layout queries on the host)
 int compute_units();
