@@ -17,7 +17,10 @@
  *     sized by wlb_attn_workspace_size().
  *   - Host calls are synchronous.  Device calls only enqueue work on `stream`
  *     (a hipStream_t passed as void*, NULL = the default stream) and return; they
- *     never synchronise and never allocate.
+ *     never synchronise and never allocate.  They issue kernel launches only (no
+ *     memset, no copy), so a caller may capture them into a HIP graph and replay it.
+ *     Calls that share a workspace must be ordered on their stream(s): the schedule,
+ *     partial results and per-row scratch in it are rewritten by every call.
  *   - Token indices and offsets are int32 (T < 2^31); pair counts and costs are 64-bit.
  *   - bf16 tensors are passed as void* to 2-byte elements, row-major, token-major:
  *     Q, O, dO, dQ are [n_q][hq][head_dim]; K, V, dK, dV are [t_kv][hkv][head_dim];
@@ -235,8 +238,9 @@ typedef struct {
     size_t  off_key_slot_base;           /* int32 [n_key_tiles + 1]: first partial slot of the tile of rank r */
     /* forward / dQ work: the query tiles in order, each repeated for every KV head, form one line of
        work measured in key tiles (plus a fixed per-tile cost); row_gangs gangs of hq/hkv workgroups
-       take equal consecutive shares of it, so a tile cut by a share's end is finished by the next gang
-       and the parts are merged from fp32 partial results */
+       take consecutive shares of it (the first half of the gangs, whose workgroups run faster, a
+       somewhat larger one), so a tile cut by a share's end is finished by the next gang and the
+       parts are merged from fp32 partial results */
     int32_t row_gangs;
     size_t  off_fwd_prefix;              /* int64 [n_fwd_tiles + 1]: cost of the query tiles before order rank r */
     size_t  plan_bytes;
