@@ -54,6 +54,32 @@ def test_forward_all_padding_rows():
     assert (o == 0).all() and np.isneginf(lse).all()
 
 
+def test_out_of_range_row_indices_are_padding():
+    """q_idx entries outside [0, t_kv) other than -1 are treated like -1 (stated in the header)."""
+    import torch
+    docs = [200, 57, 1]
+    t = sum(docs)
+    w, tens = wl.small_case(33, docs, 2, 1, 64)
+    clean = np.arange(t, dtype=np.int32)
+    bad = np.array([3, 64, 199, 200, 256, 257], dtype=np.int64)
+    clean[bad] = -1
+    c = Case(tens, clean, _cu(docs), 2, 1, 64, w.scale)
+    dirty = clean.copy()
+    dirty[bad] = np.array([-5, t, t + 1000, 2**31 - 1, -2**31, -2], dtype=np.int64).astype(np.int32)
+    c.attn.q_idx.copy_(torch.from_numpy(dirty))
+    c.check_fwd()
+    c.check_bwd()
+
+
+def test_one_token():
+    for d in (64, 128):
+        c = _small(34, [1], 1, 1, d)
+        o, lse = c.run_fwd()
+        assert np.array_equal(o[0, 0], c.f64("v")[0, 0])          # a one-token document returns its own V
+        c.check_fwd()
+        c.check_bwd()
+
+
 def test_forward_rows_in_arbitrary_order():
     # the mask is per row; nothing requires q_idx to be sorted
     docs = [200, 333, 90]
