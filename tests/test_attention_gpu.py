@@ -105,13 +105,13 @@ def test_forward_is_deterministic_and_plan_reuse_changes_nothing():
     assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
 
 
-@pytest.mark.parametrize("hq,hkv,d", [(4, 2, 128), (6, 2, 64), (12, 1, 128), (3, 3, 64)])
+@pytest.mark.parametrize("hq,hkv,d", [(4, 2, 128), (6, 2, 64), (12, 1, 128), (3, 3, 64), (16, 1, 128), (32, 2, 64)])
 @pytest.mark.parametrize("flag", [B.ATTN_SCHEDULE_GANGS, B.ATTN_SCHEDULE_ITEMS])
 def test_both_row_schedules_match_oracle(flag, hq, hkv, d):
     """Forward and dQ have two work schedules (fixed gangs with tiles cut at share ends and merged
     from partial results / one workgroup per tile and head); both forced here on an input with
     documents from 1 token to several tiles, pads, and tiles that straddle documents, for head
-    groups of 1, 2, 3 and 12 query heads per KV head and both head dimensions."""
+    groups of 1, 2, 3, 12 and 16 query heads per KV head and both head dimensions."""
     docs = [900, 1, 37, 2600, 130, 64, 700]
     w, tens = wl.small_case(77, docs, hq, hkv, d)
     for cp, r in ((1, 0), (2, 1)):
