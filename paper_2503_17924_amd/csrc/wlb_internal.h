@@ -39,11 +39,9 @@ inline int row_gangs(int hq, int hkv, int cus) {
 }
 // fixed cost of a query tile (loading Q, the first copies, the output) in units of one key tile's work
 constexpr int kRowItemOverhead = 6;
-// relative work shares of a gang of the first and of the second half of a forward / dQ launch
-#ifndef WLB_ROW_SHARE_FIRST
-#define WLB_ROW_SHARE_FIRST 58
-#endif
-constexpr int kRowShareFirst = WLB_ROW_SHARE_FIRST, kRowShareSecond = 100 - WLB_ROW_SHARE_FIRST;
+// relative work share (percent) of a gang of the first half of a launch; a gang of the second half
+// gets the rest (measured optimum: forward 56, dQ 58)
+constexpr int kRowShareFirstFwd = 56, kRowShareFirstDq = 58;
 // Which of the two forward / dQ schedules a launch uses: gangs with fixed shares when there are fewer
 // than kRowGangMaxItemsPerSlot (query tile, head) items per workgroup slot and an estimated
 // kRowGangMinUnitsPerSlot key tiles of work per slot, else one workgroup per item.  The
