@@ -28,9 +28,9 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 COST_A, COST_B = 6, 640000    # packer cost model, picoseconds per token^2 / per token
 # HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size), measured with
 # rocprofv3 --pmc on this workload: profiles/hbm_traffic_c2_128k_cp8.txt
-MEASURED_TRAFFIC_BYTES = {("c2_128k_cp8", "dkv_kernel"): int((4.178 + 0.246) * 2**30),
-                          ("c2_128k_cp8", "dq_kernel"): int((3.009 + 0.077) * 2**30),
-                          ("c2_128k_cp8", "fwd_kernel"): int((2.954 + 0.078) * 2**30)}
+MEASURED_TRAFFIC_BYTES = {("c2_128k_cp8", "dkv_kernel"): int((4.214 + 0.246) * 2**30),
+                          ("c2_128k_cp8", "dq_kernel"): int((3.010 + 0.077) * 2**30),
+                          ("c2_128k_cp8", "fwd_kernel"): int((2.982 + 0.078) * 2**30)}
 
 
 def parse():
