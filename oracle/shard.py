@@ -38,7 +38,11 @@ Readings where the paper is silent (all shared with the C library by design):
 Pins (tests/test_oracle_shard.py): all ranks' real entries partition [0, T);
 equal slot counts; the closed-form pair count (2CP-1)c^2 + c(c+1) per rank when
 2*CP | L; CP = 1 identity; single document with 2*CP | L gives the same map in
-both modes; hand-worked small examples under tests/golden/.
+both modes; hand-worked small examples under tests/golden/ (q_idx of every mode,
+and cu_seqlens_q / seg_k_begin / seg_k_end of every mode, the round-robin remainder
+runs of the padding-free mode included); the segment arrays of all three modes
+against their definition (maximal runs of consecutive tokens of one chunk of one
+document, seg_k_end one past the last real token).
 """
 from __future__ import annotations
 

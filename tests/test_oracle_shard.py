@@ -15,17 +15,32 @@ def _golden_cases():
         line = line.strip()
         if not line or line.startswith("#"):
             continue
-        head, docs, exp = [x.strip() for x in line.split("|")]
+        fields = [x.strip() for x in line.split("|")]
+        head, docs, exp = fields[:3]
         mode, cp, rank = head.split()
+        segs = [[int(x) for x in f.split()] for f in fields[3:]]
+        assert len(segs) in (0, 3), line
         out.append(({"per_doc": osh.PER_DOC_PADDED, "per_seq": osh.PER_SEQ, "per_doc_nopad": osh.PER_DOC_NOPAD}[mode], int(cp), int(rank),
-                    [int(x) for x in docs.split()], [int(x) for x in exp.split()]))
+                    [int(x) for x in docs.split()], [int(x) for x in exp.split()], segs))
     return out
 
 
-@pytest.mark.parametrize("mode,cp,rank,docs,exp", _golden_cases())
-def test_hand_worked_examples(mode, cp, rank, docs, exp):
+@pytest.mark.parametrize("mode,cp,rank,docs,exp,segs", _golden_cases())
+def test_hand_worked_examples(mode, cp, rank, docs, exp, segs):
     r = osh.shard(docs, cp, rank, mode)
     assert r["q_idx"].tolist() == exp
+    if segs:
+        assert r["cu_seqlens_q"].tolist() == segs[0]
+        assert r["seg_k_begin"].tolist() == segs[1]
+        assert r["seg_k_end"].tolist() == segs[2]
+
+
+def test_golden_file_pins_the_segments_of_every_mode():
+    modes = {m for m, _, _, _, _, segs in _golden_cases() if segs}
+    assert modes == {osh.PER_DOC_PADDED, osh.PER_SEQ, osh.PER_DOC_NOPAD}
+    # and a rank that holds two non-adjacent remaining tokens of one document (padding-free mode)
+    assert any(m == osh.PER_DOC_NOPAD and segs and len(segs[1]) != len(set(segs[1])) and
+               any(b - a == 1 for a, b in zip(segs[0], segs[0][1:])) for m, _, _, _, _, segs in _golden_cases())
 
 
 def _rand_docs(rng, n, hi):
@@ -96,24 +111,74 @@ def test_single_divisible_document_same_in_both_modes():
                 assert a[key].tolist() == b[key].tolist()
 
 
-def test_segments_describe_the_rows():
-    docs = [5, 12, 1, 30]
-    for mode in (osh.PER_DOC_PADDED, osh.PER_SEQ):
-        dl = list(docs)
-        for r in range(2):
-            out = osh.shard(dl, 2, r, mode)
-            cu_k = out["cu_seqlens_k"]
-            for s in range(len(out["seg_k_begin"])):
-                rows = out["q_idx"][out["cu_seqlens_q"][s]:out["cu_seqlens_q"][s + 1]]
-                real = rows[rows >= 0]
-                kb, ke = out["seg_k_begin"][s], out["seg_k_end"][s]
-                assert kb in cu_k.tolist()
-                if len(real):
-                    d = np.searchsorted(cu_k, real, side="right") - 1
-                    assert (cu_k[d] == kb).all()          # one document per segment
-                    assert ke == real.max() + 1
-                else:
-                    assert ke == kb
+def _chunk_of(mode, cp, docs, tok):
+    """The definition, written out for one token: (document, chunk) it belongs to; chunk -1 = one of a
+    document's remaining tokens in the padding-free mode."""
+    cu = np.concatenate([[0], np.cumsum(docs)])
+    d = int(np.searchsorted(cu, tok, side="right") - 1)
+    n = 2 * cp
+    if cp == 1:
+        return d, 0
+    if mode == osh.PER_SEQ:
+        return d, tok // (cu[-1] // n)
+    L, p = docs[d], tok - cu[d]
+    if mode == osh.PER_DOC_PADDED:
+        return d, p // -(-L // n)
+    c = L // n
+    return d, (p // c if p < c * n else -1)
+
+
+@pytest.mark.parametrize("mode", [osh.PER_DOC_PADDED, osh.PER_SEQ, osh.PER_DOC_NOPAD])
+@pytest.mark.parametrize("cp,docs", [(2, [5, 12, 1, 30]), (3, [7, 29, 2, 64, 11, 1, 6]), (4, [3, 50, 21, 9, 13])])
+def test_segments_describe_the_rows(mode, cp, docs):
+    """cu_seqlens_q / seg_k_begin / seg_k_end against their definition: the segments tile the slots in
+    order; the real rows of a segment are consecutive tokens of one chunk of one document; two segments in
+    a row differ in document or chunk or are separated by a gap (maximal runs); seg_k_begin is the
+    document's start and seg_k_end one past the segment's last real token."""
+    docs = list(docs)
+    total = sum(docs)
+    if mode == osh.PER_SEQ and total % (2 * cp):
+        docs[-1] += 2 * cp - total % (2 * cp)
+    for r in range(cp):
+        out = osh.shard(docs, cp, r, mode)
+        cu_k, cu_q = out["cu_seqlens_k"], out["cu_seqlens_q"]
+        assert cu_q[0] == 0 and cu_q[-1] == len(out["q_idx"]) and (np.diff(cu_q) > 0).all()
+        assert len(out["seg_k_begin"]) == len(out["seg_k_end"]) == len(cu_q) - 1
+        prev = None
+        for s in range(len(out["seg_k_begin"])):
+            rows = out["q_idx"][cu_q[s]:cu_q[s + 1]]
+            real = rows[rows >= 0]
+            kb, ke = out["seg_k_begin"][s], out["seg_k_end"][s]
+            assert kb in cu_k.tolist()
+            if mode == osh.PER_DOC_NOPAD:
+                assert len(real) == len(rows)
+            if not len(real):
+                assert ke == kb
+                prev = None
+                continue
+            assert (np.diff(real) == 1).all()                     # consecutive tokens
+            assert (rows[:len(real)] >= 0).all()                  # padding only at a segment's end
+            keys = {_chunk_of(mode, cp, docs, int(t)) for t in real}
+            assert len(keys) == 1                                 # one chunk of one document
+            d, chunk = next(iter(keys))
+            assert cu_k[d] == kb and ke == real.max() + 1
+            if chunk >= 0:
+                assert chunk in (r, 2 * cp - 1 - r) or cp == 1
+            # maximal: the segment before it is another (document, chunk) or does not end right before it
+            if prev is not None and prev[0] == (d, chunk):
+                assert prev[1] + 1 < real[0]
+            prev = ((d, chunk), int(real[-1]))
+
+
+def test_padding_free_pair_count_is_the_sum_over_the_rows():
+    docs = [7, 29, 2, 64, 11, 1, 6]
+    for cp in (2, 3):
+        cu = np.concatenate([[0], np.cumsum(docs)])
+        for r in range(cp):
+            out = osh.shard(docs, cp, r, osh.PER_DOC_NOPAD)
+            q = out["q_idx"]
+            want = int((q - cu[np.searchsorted(cu, q, side="right") - 1] + 1).sum())
+            assert out["useful_pairs"] == want
 
 
 def test_per_sequence_is_imbalanced_per_document_is_not():
