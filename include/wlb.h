@@ -252,7 +252,9 @@ wlb_status wlb_attn_plan_layout(const wlb_attn_desc* desc, wlb_plan_layout* layo
  * outputs o [n_q][hq][D] bf16 and lse [hq][n_q] float are overwritten.
  * Errors: INVALID_ARG (null pointer, bad desc), UNSUPPORTED (head_dim; Q or K of 4 GiB or more,
  * counting 128 rows past the end: the kernels address tensors with 32-bit offsets), BUFFER_TOO_SMALL,
- * HIP (launch failure).  Nothing is launched when an error is returned. */
+ * HIP (launch failure).  Argument errors are found before anything is enqueued; after a HIP
+ * error the stream may already hold the kernels launched before the failing one (the schedule's,
+ * unless WLB_ATTN_REUSE_PLAN is set), and the outputs and the workspace are undefined. */
 wlb_status wlb_attn_fwd(const wlb_attn_desc* desc, const void* q, const void* k, const void* v,
                         const int32_t* q_idx, const int32_t* cu_seqlens_k,
                         void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream);

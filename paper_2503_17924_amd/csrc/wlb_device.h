@@ -228,12 +228,16 @@ struct BufRsrc {
 // One buffer_load_dwordx4 ... lds: 64 lanes x 16 bytes from (descriptor base + soff + voff)
 // into LDS at lds_addr + 16*lane.  Written as inline assembly so that the compiler does not
 // serialise later LDS reads of OTHER buffers behind this copy; the callers order reads of the
-// destination buffer themselves (wait_vmem + barrier).
+// destination buffer themselves (wait_vmem + barrier).  The statement writes m0 (the LDS base of
+// the copy) and says so in its clobber list; the compiler's remark that m0 is a reserved
+// register is expected and switched off for these two statements.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma_issue_1k(const i32x4& rsrc, uint32_t lds_addr, int voff, uint32_t soff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 template <int D, int ROWS, int NW>
@@ -274,8 +278,10 @@ __device__ __forceinline__ void dma_issue_256(const i32x4& rsrc, uint32_t lds_ad
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
-                 : "memory");
+                 : "memory", "m0");
 }
+
+#pragma clang diagnostic pop
 
 // wait until at most N of this wavefront's most recent vector-memory operations are outstanding
 template <int N>

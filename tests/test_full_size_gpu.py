@@ -208,7 +208,60 @@ def test_config3_pack_then_attention():
     dq, dk, dv = c.run_bwd()
     rows = _rows_sample(c.q_idx, c.cu_k, 16, np.random.default_rng(3))
     _check_rows(c, o, lse, dq, rows, "micro-batch")
+    # dK/dV element by element: every document of up to 4096 tokens whole (at CP = 1 a document's keys are
+    # seen by its own rows only), and the last 512 keys of the longer ones
+    cu = c.cu_k
+    for dd in range(len(cu) - 1):
+        L = cu[dd + 1] - cu[dd]
+        lo = cu[dd] if L <= 4096 else cu[dd + 1] - 512
+        _check_dkv_for_rows(c, dk, dv, np.arange(lo, cu[dd + 1]), lo, cu[dd + 1], f"document {dd}")
     _check_identities(c, dq, dk, dv)
+
+
+def _dkv_item_table(c):
+    """(items per key tile, stages per item) of the dK/dV schedule in the case's workspace."""
+    lay = B.wlb_attn_plan_layout(c.attn.desc)
+    ws = c.attn.workspace.cpu().numpy()
+    arr = lambda off, n: ws[off:off + 4 * n].view(np.int32)
+    ways = arr(lay.off_key_ways, lay.n_key_tiles)
+    krange = arr(lay.off_key_range, 2 * lay.n_key_tiles).reshape(-1, 2)
+    stages = (krange[:, 1] - krange[:, 0]) * ((c.hq // c.hkv) // ways)
+    return ways, stages
+
+
+@pytest.mark.parametrize("docs,cp,rank,min_stages", [([20480, 900, 37, 3000, 1], 2, 0, 150), ([700, 12288, 5, 2100], 1, 0, 150)])
+def test_whole_long_document_every_gradient_element(docs, cp, rank, min_stages):
+    """Every element of dQ, dK and dV of a long document against the oracle, at head_dim 128 with 8 query
+    heads per KV head.  The document is long enough that its key tiles are divided by heads into 2, 4 and 8
+    dK/dV work items (fp32 partial results summed by the fix-up pass) and that an item streams more than 150
+    stages (row group x head) through the three stage buffers; both work schedules of the forward / dQ kernels run."""
+    hq, hkv, d = 8, 1, 128
+    w, tens = wl.small_case(131, docs, hq, hkv, d)
+    sh = B.wlb_shard(np.asarray(docs, dtype=np.int32), cp, rank, B.SHARD_PER_DOC_PADDED)
+    c = Case(tens, sh["q_idx"], sh["cu_seqlens_k"], hq, hkv, d, w.scale)
+    real = c.q_idx >= 0
+    rows = _rows_sample(c.q_idx, c.cu_k, 64, np.random.default_rng(131))
+    ref = None
+    for flags in (B.ATTN_SCHEDULE_GANGS, B.ATTN_SCHEDULE_ITEMS):
+        c.flags = flags
+        o, lse = c.run_fwd()
+        dq, dk, dv = c.run_bwd()
+        if ref is None:
+            ways, stages = _dkv_item_table(c)
+            assert {2, 4, 8} <= set(ways.tolist()), "the key tiles of this input must be split 2, 4 and 8 ways"
+            assert stages[ways > 1].max() > min_stages, "a split item must stream more than 150 stages"
+            ref = c.oracle_bwd()
+        _check_rows(c, o, lse, None, rows, f"flags {flags}")
+        check_close(f"dQ flags {flags}", dq, ref[0], rows=real)
+        check_close(f"dK flags {flags}", dk, ref[1])
+        check_close(f"dV flags {flags}", dv, ref[2])
+        # per key tile as well: an error confined to one work item must not hide in the tensor-wide mean
+        for name, got, want in (("dK", dk, ref[1]), ("dV", dv, ref[2])):
+            scale = np.abs(want).max()
+            err = np.abs(got - want).reshape(len(got), -1)
+            tile_mean = np.add.reduceat(err.mean(axis=1), np.arange(0, len(got), 128)) / 128
+            assert tile_mean.max() / scale <= 2e-3, f"{name}: key tile {int(tile_mean.argmax())} mean err {tile_mean.max() / scale:.3e}"
+        assert (dq[~real] == 0).all()
 
 
 def test_tensors_close_to_the_4gib_limit():
