@@ -259,6 +259,28 @@ wlb_status wlb_attn_fwd(const wlb_attn_desc* desc, const void* q, const void* k,
                         const int32_t* q_idx, const int32_t* cu_seqlens_k,
                         void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The same forward as
+ * wlb_attn_fwd with its scratch -- the schedule tables -- in a fixed device array of
+ * WLB_ATTN_FWD_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the process
+ * ends) instead of a caller's workspace.  The call allocates nothing and launches the same kernels;
+ * it always uses the one-workgroup-per-(query tile, head) schedule, which leaves no partial results.
+ * Arguments as wlb_attn_fwd.  flags: WLB_ATTN_REUSE_PLAN means the array still holds the schedule
+ * that the previous wlb_attn_fwd_static call on this GPU built for the same desc, q_idx and
+ * cu_seqlens_k (every layer of a model shares one mask); WLB_ATTN_SCHEDULE_ITEMS is implied; any
+ * other flag is INVALID_ARG.  Nothing in the array has to start at zero: each call without
+ * WLB_ATTN_REUSE_PLAN rewrites every table it reads.
+ * Limit: UNSUPPORTED when the schedule of (n_q, t_kv) is larger than the array -- it holds about
+ * 8.2 bytes per query row and 0.2 bytes per key, so e.g. n_q = t_kv = 131072 (1.1 MiB) fits and
+ * n_q above about 240000 does not.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams,
+ * two threads) race on it and must be ordered by the caller.  The first call on a GPU looks up the
+ * array's address (no allocation); make that call outside graph capture. */
+#define WLB_ATTN_FWD_STATIC_SCRATCH_BYTES (2u << 20)
+wlb_status wlb_attn_fwd_static(const wlb_attn_desc* desc, const void* q, const void* k, const void* v,
+                               const int32_t* q_idx, const int32_t* cu_seqlens_k,
+                               void* o, float* lse, void* stream);
+
 /* Backward.  Takes the forward's o and lse plus d_o [n_q][hq][D]; overwrites dq [n_q][hq][D],
  * dk and dv [t_kv][hkv][D] (bf16) with THIS call's rows' contribution (a CP rank's partial;
  * keys no local row can see get 0).  Deterministic: no atomics. */

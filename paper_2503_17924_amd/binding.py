@@ -33,7 +33,7 @@ STATUS_NAMES = {0: "WLB_OK", 1: "WLB_ERR_INVALID_ARG", 2: "WLB_ERR_BUFFER_TOO_SM
 
 EXPORTS = ["wlb_last_error", "wlb_pack", "wlb_pack_optimal", "wlb_packer_create", "wlb_packer_destroy", "wlb_packer_step",
            "wlb_packer_pending", "wlb_calib_mfma", "wlb_predict_latency", "wlb_select_sharding", "wlb_shard_size", "wlb_shard", "wlb_attn_workspace_size",
-           "wlb_attn_plan", "wlb_attn_plan_layout", "wlb_attn_fwd", "wlb_attn_bwd"]
+           "wlb_attn_plan", "wlb_attn_plan_layout", "wlb_attn_fwd", "wlb_attn_fwd_static", "wlb_attn_bwd"]
 
 
 class WlbError(RuntimeError):
@@ -297,6 +297,14 @@ def wlb_attn_fwd(desc, q, k, v, q_idx, cu_seqlens_k, o, lse, workspace):
                               _dev_ptr(q_idx, torch.int32), _dev_ptr(cu_seqlens_k, torch.int32),
                               _dev_ptr(o, bf), _dev_ptr(lse, torch.float32), _dev_ptr(workspace),
                               C.c_size_t(workspace.numel() * workspace.element_size()), _stream()))
+
+
+def wlb_attn_fwd_static(desc, q, k, v, q_idx, cu_seqlens_k, o, lse):
+    import torch
+    bf = torch.bfloat16
+    _check(lib().wlb_attn_fwd_static(C.byref(desc), _dev_ptr(q, bf), _dev_ptr(k, bf), _dev_ptr(v, bf),
+                                     _dev_ptr(q_idx, torch.int32), _dev_ptr(cu_seqlens_k, torch.int32),
+                                     _dev_ptr(o, bf), _dev_ptr(lse, torch.float32), _stream()))
 
 
 def wlb_attn_bwd(desc, q, k, v, o, lse, d_o, q_idx, cu_seqlens_k, dq, dk, dv, workspace):

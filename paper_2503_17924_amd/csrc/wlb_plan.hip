@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <mutex>
 
 #include "wlb_device.h"
 #include "wlb_internal.h"
@@ -388,6 +389,35 @@ wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const i
     return WLB_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// Scratch of wlb_attn_fwd_static: the schedule tables live in this array instead of a caller's
+// workspace.  Every GPU the library runs on holds its own copy, at its own address, until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the address
+// that call returns (kept per device) is what kernels and every other use of the memory get.
+static __device__ __align__(256) unsigned char scratch[WLB_ATTN_FWD_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];      // device address of `scratch` on each device, once resolved
+static std::mutex g_scratch_mutex;
+
+// The current device's copy of `scratch`; resolved on the first call on that device.
+static wlb_status static_scratch(char** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(WLB_ERR_HIP, "wlb_attn_fwd_static: hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(WLB_ERR_UNSUPPORTED, "wlb_attn_fwd_static: device %d (at most %d devices)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(WLB_ERR_HIP, "wlb_attn_fwd_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = (char*)g_scratch_ptr[dev];
+    return WLB_OK;
+}
+
 // delta and the log2-scaled LSE copy, [hq][n_q] floats each
 static size_t delta_bytes(const wlb_attn_desc& d) { return 2 * align_up(sizeof(float) * (size_t)d.hq * d.n_q, 256); }
 
@@ -438,6 +468,31 @@ extern "C" wlb_status wlb_attn_fwd(const wlb_attn_desc* desc, const void* q, con
     if (!reuse)
         if (wlb_status st = launch_plan(*desc, L, q_idx, cu_seqlens_k, (char*)workspace, stream)) return st;
     return launch_fwd(*desc, L, q, k, v, o, lse, (char*)workspace, L.plan_bytes, stream);
+}
+
+extern "C" wlb_status wlb_attn_fwd_static(const wlb_attn_desc* desc, const void* q, const void* k, const void* v,
+                                          const int32_t* q_idx, const int32_t* cu_seqlens_k, void* o, float* lse,
+                                          void* stream) {
+    if (wlb_status st = check_desc(desc)) return st;
+    if (!q || !k || !v || !o || !lse) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_fwd_static: null pointer");
+    if (desc->flags & ~(WLB_ATTN_REUSE_PLAN | WLB_ATTN_SCHEDULE_ITEMS))
+        return fail(WLB_ERR_INVALID_ARG, "wlb_attn_fwd_static: flags 0x%x (only WLB_ATTN_REUSE_PLAN and WLB_ATTN_SCHEDULE_ITEMS apply)", desc->flags);
+    const bool reuse = desc->flags & WLB_ATTN_REUSE_PLAN;
+    if (!reuse && (!q_idx || !cu_seqlens_k)) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_fwd_static: null q_idx/cu_seqlens_k");
+    // one workgroup per (query tile, head): the schedule that leaves no partial results, so the
+    // schedule tables are all the scratch the call needs
+    wlb_attn_desc d = *desc;
+    d.flags |= WLB_ATTN_SCHEDULE_ITEMS;
+    wlb_plan_layout L;
+    plan_layout(d, &L);
+    if (L.plan_bytes > (size_t)WLB_ATTN_FWD_STATIC_SCRATCH_BYTES)
+        return fail(WLB_ERR_UNSUPPORTED, "wlb_attn_fwd_static: the schedule of n_q=%d, t_kv=%d needs %zu bytes, the library's array holds %zu",
+                    d.n_q, d.t_kv, L.plan_bytes, (size_t)WLB_ATTN_FWD_STATIC_SCRATCH_BYTES);
+    char* ws = nullptr;
+    if (wlb_status st = static_scratch(&ws)) return st;
+    if (!reuse)
+        if (wlb_status st = launch_plan(d, L, q_idx, cu_seqlens_k, ws, stream)) return st;
+    return launch_fwd(d, L, q, k, v, o, lse, ws, L.plan_bytes, stream);
 }
 
 extern "C" wlb_status wlb_attn_bwd(const wlb_attn_desc* desc, const void* q, const void* k, const void* v,
