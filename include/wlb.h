@@ -197,7 +197,12 @@ enum {
     /* The forward and dQ kernels have two work schedules (see wlb_plan_layout: row_gangs); the
      * library picks one from the shape.  These flags force one of them (tests, measurements). */
     WLB_ATTN_SCHEDULE_GANGS = 32,
-    WLB_ATTN_SCHEDULE_ITEMS = 64
+    WLB_ATTN_SCHEDULE_ITEMS = 64,
+    /* In the one-workgroup-per-item schedule, query tiles whose rows see only a short run of keys
+     * (documents of a few dozen tokens: the short-chunk case of Section 5.2) go to kernels that
+     * keep that run of K/V in LDS for all query heads of a KV head.  This flag sends every tile
+     * through the general kernels instead (tests, measurements). */
+    WLB_ATTN_NO_SHORT_PATH = 128
 };
 
 /* Bytes of device workspace needed (256-byte aligned pointer expected).  The forward needs
@@ -243,6 +248,11 @@ typedef struct {
        parts are merged from fp32 partial results */
     int32_t row_gangs;
     size_t  off_fwd_prefix;              /* int64 [n_fwd_tiles + 1]: cost of the query tiles before order rank r */
+    /* short-hull path: per block of 32 slots the hull {k_lo, k_hi} of the keys its real rows see (k_hi <= k_lo:
+       no real row), and per query tile whether each of its blocks' hulls fits the short-hull kernels' LDS window */
+    int32_t n_blocks32;
+    size_t  off_block_hull;              /* int32 [n_blocks32][2] */
+    size_t  off_tile_short;              /* int32 [n_fwd_tiles]: 1 = short-hull tile */
     size_t  plan_bytes;
 } wlb_plan_layout;
 

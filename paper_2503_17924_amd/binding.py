@@ -27,6 +27,7 @@ ATTN_BWD_SKIP_DQ = 4
 ATTN_BWD_SKIP_DKV = 8
 ATTN_SCHEDULE_GANGS = 32
 ATTN_SCHEDULE_ITEMS = 64
+ATTN_NO_SHORT_PATH = 128
 
 STATUS_NAMES = {0: "WLB_OK", 1: "WLB_ERR_INVALID_ARG", 2: "WLB_ERR_BUFFER_TOO_SMALL",
                 3: "WLB_ERR_UNSUPPORTED", 4: "WLB_ERR_HIP"}
@@ -55,6 +56,7 @@ class PlanLayout(C.Structure):
                 ("off_key_range", C.c_size_t), ("dkv_max_items", C.c_int32), ("dkv_max_partials", C.c_int32),
                 ("off_key_ways", C.c_size_t), ("off_key_item_base", C.c_size_t), ("off_key_slot_base", C.c_size_t),
                 ("row_gangs", C.c_int32), ("off_fwd_prefix", C.c_size_t),
+                ("n_blocks32", C.c_int32), ("off_block_hull", C.c_size_t), ("off_tile_short", C.c_size_t),
                 ("plan_bytes", C.c_size_t)]
 
 

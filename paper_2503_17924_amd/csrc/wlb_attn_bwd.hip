@@ -41,6 +41,8 @@ struct BwdParams {
     float* partial;
     RowSched sched;            // dQ: which query tiles, heads and key ranges a workgroup works on
     float* row_partial;        // dQ: partial results of the tiles cut at a gang boundary
+    const int32_t* block_hull; const int32_t* tile_short;   // short-hull path (see dq_short_kernel)
+    int n_blocks32, use_short, delta_skips_short;
     int n_q, t_kv, hq, hkv, n_groups, n_tiles, n_key_tiles;
     float scale_log2e, scale;
 };
@@ -52,7 +54,9 @@ __global__ void __launch_bounds__(256) delta_kernel(const BwdParams p) {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     const size_t rh = idx / LPR;                     // row * hq + head
     const int c = (int)(idx % LPR);
-    const size_t total = (size_t)p.n_q * p.hq;
+    size_t total = (size_t)p.n_q * p.hq;
+    // rows of short-hull tiles get delta and the LSE copy from dq_short_kernel
+    if (p.delta_skips_short && rh < total && p.tile_short[(rh / p.hq) / kFwdTileRows]) total = 0;
     float acc = 0.f;
     if (rh < total) {
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(p.d_o + rh * D + c * 8);
@@ -325,9 +329,239 @@ __global__ void __launch_bounds__(256, 2) dq_items_kernel(const BwdParams p) {
     const int rank = (y / p.hkv) * 8 + x;
     if (rank >= p.n_tiles) return;
     pc.tile = ld_const(p.sched.order + rank);
+    if (p.use_short && ld_const(p.tile_short + pc.tile)) return;     // dq_short_kernel's tile
     pc.c = (int)(ld_const64(p.sched.prefix + rank + 1) - ld_const64(p.sched.prefix + rank));
     pc.a = 0; pc.b = pc.c; pc.slot = -1;
     dq_piece<D>(p, smem, pc);
+}
+
+// dQ of short-hull tiles, the counterpart of the forward's short-hull kernel (same workgroup shape,
+// same LDS layout: K window | V window | one staging tile per wavefront; see there).  A wavefront
+// works on one query head at a time; that head's rows of Q and dO reach it as whole rows -- held in
+// registers while the head before is computed -- and pass through the staging tile into the MFMA
+// operand layout.  All keys a row sees lie inside the window, so the wavefront has the row's whole
+// P and dP and forms delta itself as sum_j P_ij dP_ij (equal to <dO_i, O_i> since O = P V), without
+// reading O: first pass per 32-key block S^T, dP^T, P and X = P o dP (both kept as bf16), then
+// dS^T = X - delta P and dQ^T += K^T dS^T.  delta (negated) and the log2-scaled LSE copy are left
+// for the dK/dV kernel, which runs after this one; the separate delta pass skips these rows.
+template <int D>
+__global__ void __launch_bounds__(256, 2) dq_short_kernel(const BwdParams p) {
+    constexpr int NW = 4, KS = D / 16, DB = D / 32, CPR = D / 8, ROWB = D * 2;
+    constexpr int HULL = kShortHullKeys, NB = HULL / 32, STAGE = kShortBlockRows * ROWB, RPI = 64 / CPR;
+    __shared__ __attribute__((aligned(1024))) char smem[2 * HULL * ROWB + NW * STAGE];
+
+    const int G = p.hq / p.hkv;
+    const int per_xcd = (p.n_blocks32 + 7) / 8;
+    const int x = blockIdx.x & 7, jj = blockIdx.x >> 3;
+    const int blk = x * per_xcd + jj / p.hkv, hk = jj % p.hkv;
+    if (jj / p.hkv >= per_xcd || blk >= p.n_blocks32) return;
+    if (!ld_const(p.tile_short + blk / (kFwdTileRows / kShortBlockRows))) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const int j16 = lane & 15, gi = (lane >> 4) & 1;
+    const int h_lo = ld_const(p.block_hull + 2 * blk), h_hi = ld_const(p.block_hull + 2 * blk + 1);
+    const int row0 = blk * kShortBlockRows;
+    const int row = row0 + l32;
+    const bool in = row < p.n_q;
+    const int rc = in ? row : p.n_q - 1;
+    const uint32_t q_row = (uint32_t)p.hq * D;
+
+    const uint32_t q_row_bytes = q_row * 2u;
+    const buf_rsrc_t q_buf = make_buf(p.q, (uint32_t)p.n_q * q_row_bytes), do_buf = make_buf(p.d_o, (uint32_t)p.n_q * q_row_bytes),
+                     dq_buf = make_buf(p.dq, (uint32_t)p.n_q * q_row_bytes);
+    const int row_voff = RowBlock<D>::lane_off(lane, q_row_bytes);
+    auto head_soff = [&](int hs) { return uniform((uint32_t)row0 * q_row_bytes + (uint32_t)(hk * G + hs) * ROWB); };
+
+    if (h_hi <= h_lo) {
+        // no real row in this block: dQ = 0; delta = 0 and LSE copy = +inf keep the rows out of dK/dV
+        RowBlock<D> zero;
+#pragma unroll
+        for (int i = 0; i < RowBlock<D>::N; ++i) zero.v[i] = i32x4{0, 0, 0, 0};
+        for (int hs = wave; hs < G; hs += NW) {
+            const int h = hk * G + hs;
+            zero.store(dq_buf, row_voff, head_soff(hs), q_row_bytes);
+            if (in && half == 0) {
+                p.delta[(size_t)h * p.n_q + row] = 0.f;
+                p.lse2[(size_t)h * p.n_q + row] = INFINITY;
+            }
+        }
+        return;
+    }
+    const int kstart = h_lo & ~31;
+    const int nblk = (h_hi - kstart + 31) >> 5;
+
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
+    const uint32_t stage = uniform(smem_base + 2 * HULL * ROWB + (uint32_t)wave * STAGE);
+
+    // rows of the first head, in registers as whole rows
+    RowBlock<D> q_next, do_next;
+    if (wave < G) {
+        q_next.load(q_buf, row_voff, head_soff(wave), q_row_bytes);
+        do_next.load(do_buf, row_voff, head_soff(wave), q_row_bytes);
+    }
+
+    const uint32_t kv_row = (uint32_t)p.hkv * D;
+    const uint32_t kv_bytes = ((uint32_t)p.t_kv * kv_row - (uint32_t)hk * D) * 2u;
+    BufRsrc krs, vrs;
+    krs.init(p.k + (size_t)hk * D, kv_bytes);
+    vrs.init(p.v + (size_t)hk * D, kv_bytes);
+    TileDma<D, 32 * NW, NW> dma;                          // wavefront w copies the 32-key block w
+    dma.init(wave, lane, kv_row);
+    if (wave < nblk) {
+        dma.issue(krs, smem_base, kstart, wave);
+        dma.issue(vrs, smem_base + HULL * ROWB, kstart, wave);
+    }
+
+    const int lo = in ? p.row_lo[rc] : kPadLo;
+    const int hi = in ? p.row_hi[rc] : 0;
+    const bool real = hi > 0;
+    float lsec = INFINITY;
+    if (wave < G && real) lsec = p.lse[(size_t)(hk * G + wave) * p.n_q + rc] * 1.4426950408889634f;
+
+    int naddr[KS], taddr[DB][2];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) naddr[ks] = l32 * ROWB + swz<CPR>(l32, ks * 2 + half) * 16;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int key = t * 8 + half * 4 + (j16 >> 2);
+            const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
+            taddr[db][t] = smem_base + key * ROWB + swz<CPR>(key, dch) * 16 + (j16 & 1) * 8;
+        }
+    const float cs = p.scale_log2e;
+    // padding rows: zero operands and LSE = +inf make P, dS and dQ exactly 0 (their Q / dO may hold anything)
+    auto rows_from_stage = [&](bf16x8 (&dst)[KS]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 a = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(stage + naddr[ks]));
+            if (!real) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) a[i] = (__bf16)0.f;
+            }
+            dst[ks] = a;
+        }
+    };
+
+    if (wave < G) q_next.to_tile(stage, lane);
+    wait_vmem();
+    __syncthreads();              // the key window is in LDS; the wavefronts do not meet again
+
+#pragma nounroll
+    for (int hs = wave; hs < G; hs += NW) {
+        const int h = hk * G + hs;
+        const bool more = hs + NW < G;
+        bf16x8 qf[KS], dof[KS];
+        rows_from_stage(qf);                      // Q rows, written to the staging tile above / at the end of the head before
+        wait_lds();
+        do_next.to_tile(stage, lane);
+        rows_from_stage(dof);
+        const float lse_cur = lsec;
+        if (more) lsec = real ? p.lse[(size_t)(h + NW) * p.n_q + rc] * 1.4426950408889634f : INFINITY;
+
+        // first pass: P and X = P o dP of every block (masked entries 0), delta = sum of X over the row
+        bf16x8 pk[NB][2], xk[NB][2];
+        float dsum = 0.f, psum = 0.f, dsum_r = 0.f, psum_r = 0.f;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (b < nblk) {
+                f32x16 sc, dp;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 ka = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(smem_base + naddr[ks] + b * 32 * ROWB));
+                    const bf16x8 va = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(smem_base + naddr[ks] + (HULL + b * 32) * ROWB));
+                    sc = mfma32(ka, qf[ks], sc);
+                    dp = mfma32(va, dof[ks], dp);
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = kstart + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                    const float pr = (key >= lo && key < hi) ? fast_exp2(fmaf(sc[r], cs, -lse_cur)) : 0.f;
+                    sc[r] = pr;
+                    dp[r] = pr * dp[r];
+                    psum += pr;
+                    dsum += dp[r];
+                }
+#pragma unroll
+                for (int cc = 0; cc < 2; ++cc) {
+                    pk[b][cc] = pack8(sc[8 * cc + 0], sc[8 * cc + 1], sc[8 * cc + 2], sc[8 * cc + 3],
+                                      sc[8 * cc + 4], sc[8 * cc + 5], sc[8 * cc + 6], sc[8 * cc + 7]);
+                    xk[b][cc] = pack8(dp[8 * cc + 0], dp[8 * cc + 1], dp[8 * cc + 2], dp[8 * cc + 3],
+                                      dp[8 * cc + 4], dp[8 * cc + 5], dp[8 * cc + 6], dp[8 * cc + 7]);
+                    // this kernel's own delta comes from the rounded X and P that dS is formed from below, so
+                    // that they cancel exactly where they should (a row that sees one key: dS = 0)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) { dsum_r += (float)xk[b][cc][i]; psum_r += (float)pk[b][cc][i]; }
+                }
+            }
+        }
+        dsum += xhalf(dsum); psum += xhalf(psum);
+        dsum_r += xhalf(dsum_r); psum_r += xhalf(psum_r);
+        // delta_i = sum_j P_ij dP_ij / sum_j P_ij: the row's probabilities sum to 1 up to the rounding of
+        // the stored LSE, and dividing by their actual sum keeps delta equal to dP for a row with one key
+        const float delta = (real && psum_r > 0.f) ? dsum_r / psum_r : 0.f;
+        if (in && half == 0) {
+            p.delta[(size_t)h * p.n_q + row] = (real && psum > 0.f) ? -dsum / psum : 0.f;
+            p.lse2[(size_t)h * p.n_q + row] = lse_cur;
+        }
+        // dS^T = X - delta P of every block, as the bf16 operand of the second pass (in place of P)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (b < nblk) {
+#pragma unroll
+                for (int cc = 0; cc < 2; ++cc) {
+                    float ds[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) ds[i] = fmaf(-delta, (float)pk[b][cc][i], (float)xk[b][cc][i]);
+                    pk[b][cc] = pack8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
+                }
+            }
+        }
+        {
+            // the next head's rows start their way now that this head's operand registers are free; they have
+            // the second pass and the other wavefronts' work to arrive (after the last head: a load of nothing)
+            const int voff = more ? row_voff : RowBlock<D>::kNowhere;
+            q_next.load(q_buf, voff, head_soff(hs + NW), q_row_bytes);
+            do_next.load(do_buf, voff, head_soff(hs + NW), q_row_bytes);
+        }
+
+        // second pass: dQ^T += K^T dS^T
+        f32x16 acc[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (b < nblk) {
+#pragma unroll
+                for (int cc = 0; cc < 2; ++cc) {
+                    const int koff = (b * 32 + cc * 16) * ROWB;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        const bf16x8 a = cat4(lds_read_tr4_at(taddr[db][0] + koff), lds_read_tr4_at(taddr[db][1] + koff));
+                        acc[db] = mfma32(a, pk[b][cc], acc[db]);
+                    }
+                }
+            }
+        }
+        // dQ rows through the staging tile (Q and dO are in registers by now), stored as whole rows
+        const float f = real ? p.scale : 0.f;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4)
+                *reinterpret_cast<WLB_LDS bf16x4*>((uintptr_t)(stage + l32 * ROWB + swz<CPR>(l32, db * 4 + r4) * 16 + half * 8)) =
+                    pack4(acc[db][r4 * 4 + 0] * f, acc[db][r4 * 4 + 1] * f, acc[db][r4 * 4 + 2] * f, acc[db][r4 * 4 + 3] * f);
+        RowBlock<D> dq_rows;
+        dq_rows.from_tile(stage, lane);
+        dq_rows.store(dq_buf, row_voff, head_soff(hs), q_row_bytes);
+        wait_lds();                                 // the staging tile has been read back
+        q_next.to_tile(stage, lane);
+    }
 }
 
 // Sums the partial dQ of a query tile that was cut at gang boundaries.  One workgroup per
@@ -814,6 +1048,9 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.sched.n_tiles = L.n_fwd_tiles; p.sched.hkv = d.hkv; p.sched.G = d.hq / d.hkv; p.sched.n_gangs = L.row_gangs;
     p.sched.w_first = kRowShareFirstDq; p.sched.w_second = 100 - kRowShareFirstDq;
     p.row_partial = (float*)((char*)p.partial + dkv_partial_bytes(d, L));
+    p.block_hull = (const int32_t*)(ws + L.off_block_hull);
+    p.tile_short = (const int32_t*)(ws + L.off_tile_short);
+    p.n_blocks32 = L.n_blocks32;
     p.n_q = d.n_q; p.t_kv = d.t_kv; p.hq = d.hq; p.hkv = d.hkv;
     p.n_groups = L.n_groups; p.n_tiles = L.n_fwd_tiles; p.n_key_tiles = L.n_key_tiles;
     p.scale = d.scale;
@@ -829,9 +1066,14 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     const bool do_delta = !(d.flags & WLB_ATTN_BWD_SKIP_DELTA);
     const bool do_dq = !(d.flags & WLB_ATTN_BWD_SKIP_DQ);
     const bool do_dkv = !(d.flags & WLB_ATTN_BWD_SKIP_DKV);
-    if (d.head_dim == 128) { if (do_delta) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p); }
-    else { if (do_delta) delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p); }
+    p.use_short = use_short_path(d, L) ? 1 : 0;
+    // the short-hull dQ kernel forms delta for its own rows (and runs before dK/dV, which reads it);
+    // when it does not run, the delta pass covers every row
+    p.delta_skips_short = (p.use_short && do_dq) ? 1 : 0;
+    const unsigned grid_short = 8u * (unsigned)((L.n_blocks32 + 7) / 8) * (unsigned)d.hkv;
     if (d.head_dim == 128) {
+        if (do_delta) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p);
+        if (do_dq && p.use_short) dq_short_kernel<128><<<grid_short, 256, 0, stream>>>(p);
         if (do_dkv) {
             dkv_kernel<128><<<grid_dkv, 512, 0, stream>>>(p);
             dkv_fixup_kernel<128><<<grid_fix * kMergeSplit, 256, 0, stream>>>(p);
@@ -843,6 +1085,8 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
             dq_items_kernel<128><<<grid_dq_items, 256, 0, stream>>>(p);
         }
     } else {
+        if (do_delta) delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p);
+        if (do_dq && p.use_short) dq_short_kernel<64><<<grid_short, 256, 0, stream>>>(p);
         if (do_dkv) {
             dkv_kernel<64><<<grid_dkv, 512, 0, stream>>>(p);
             dkv_fixup_kernel<64><<<grid_fix * kMergeSplit, 256, 0, stream>>>(p);

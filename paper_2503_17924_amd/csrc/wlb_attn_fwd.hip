@@ -27,7 +27,8 @@ struct FwdParams {
     const int32_t* row_lo; const int32_t* row_hi; const int32_t* group;
     RowSched sched;            // which query tiles, heads and key ranges a workgroup works on
     float* partial;            // partial results of the tiles cut at a gang boundary
-    int n_q, t_kv, hq, hkv, n_groups, n_tiles;
+    const int32_t* block_hull; const int32_t* tile_short;   // short-hull path (see fwd_short_kernel)
+    int n_q, t_kv, hq, hkv, n_groups, n_tiles, n_blocks32, use_short;
     float scale_log2e, scale;
 };
 
@@ -340,9 +341,198 @@ __global__ void __launch_bounds__(256, 2) fwd_items_kernel(const FwdParams p) {
     const int rank = (y / p.hkv) * 8 + x;
     if (rank >= p.n_tiles) return;
     pc.tile = ld_const(p.sched.order + rank);
+    if (p.use_short && ld_const(p.tile_short + pc.tile)) return;     // fwd_short_kernel's tile
     pc.c = (int)(ld_const64(p.sched.prefix + rank + 1) - ld_const64(p.sched.prefix + rank));
     pc.a = 0; pc.b = pc.c; pc.slot = -1;
     fwd_piece<D>(p, smem, pc);
+}
+
+// Short-hull tiles (documents of a few dozen tokens, where a tile's rows see only the keys next to
+// them: the short-chunk case of paper Section 5.2).  There the general kernel is bound by latency:
+// per (tile, head) it fetches K/V, waits, and computes a handful of blocks.  Here a workgroup takes
+// one block of 32 rows and one KV head: it copies the (at most 96) keys the block sees into LDS
+// once -- K and V, in one shot -- and its four wavefronts then work independently, one query head
+// each at a time (heads w, w+4, ... of the KV head), with no further barrier.  Per head a wavefront
+// brings its 32 Q rows into a staging tile of its own by the same asynchronous copy (whole 256-byte
+// rows: loading the MFMA operand straight from global memory would touch 32 rows x 32 bytes per
+// instruction), computes the scores of the up to three 32-key blocks, the exact row maximum, the
+// exponentials and O^T += V^T P^T, and sends O through the staging tile so that it leaves in whole
+// rows as well.  Eight wavefronts per compute unit keep Q loads and O stores in flight; K/V
+// traffic is one LDS fill per 32 rows and KV head instead of one per head.
+template <int D>
+struct ShortTile {
+    static constexpr int KS = D / 16, DB = D / 32, CPR = D / 8, ROWB = D * 2;
+    static constexpr int HULL = kShortHullKeys, NB = HULL / 32, NW = 4;
+    static constexpr int STAGE = kShortBlockRows * ROWB;              // one wavefront's staging tile: 32 rows
+    static constexpr int LDS_BYTES = 2 * HULL * ROWB + NW * STAGE;    // K window | V window | staging tiles
+    static constexpr int RPI = 64 / CPR;                              // rows moved by one 64 x 16-byte instruction
+};
+
+template <int D>
+__global__ void __launch_bounds__(256, 2) fwd_short_kernel(const FwdParams p) {
+    using T = ShortTile<D>;
+    constexpr int NW = T::NW, KS = T::KS, DB = T::DB, CPR = T::CPR, ROWB = T::ROWB, HULL = T::HULL, NB = T::NB;
+    __shared__ __attribute__((aligned(1024))) char smem[T::LDS_BYTES];
+
+    const int G = p.hq / p.hkv;
+    // workgroup -> (block of 32 rows, KV head); XCD x takes a contiguous range of blocks, so that
+    // neighbouring blocks, whose key windows overlap, read K/V through the same L2
+    const int per_xcd = (p.n_blocks32 + 7) / 8;
+    const int x = blockIdx.x & 7, jj = blockIdx.x >> 3;
+    const int blk = x * per_xcd + jj / p.hkv, hk = jj % p.hkv;
+    if (jj / p.hkv >= per_xcd || blk >= p.n_blocks32) return;
+    if (!ld_const(p.tile_short + blk / (kFwdTileRows / kShortBlockRows))) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const int j16 = lane & 15, gi = (lane >> 4) & 1;
+    const int h_lo = ld_const(p.block_hull + 2 * blk), h_hi = ld_const(p.block_hull + 2 * blk + 1);
+    const int row0 = blk * kShortBlockRows;
+    const int row = row0 + l32;
+    const bool in = row < p.n_q;
+    const int rc = in ? row : p.n_q - 1;
+    const uint32_t q_row = (uint32_t)p.hq * D;
+
+    const uint32_t q_row_bytes = q_row * 2u;
+    const buf_rsrc_t q_buf = make_buf(p.q, (uint32_t)p.n_q * q_row_bytes), o_buf = make_buf(p.o, (uint32_t)p.n_q * q_row_bytes);
+    const int row_voff = RowBlock<D>::lane_off(lane, q_row_bytes);
+    auto head_soff = [&](int hs) { return uniform((uint32_t)row0 * q_row_bytes + (uint32_t)(hk * G + hs) * ROWB); };
+
+    if (h_hi <= h_lo) {
+        // no real row in this block: O = 0, LSE = -inf for every head of the KV head
+        RowBlock<D> zero;
+#pragma unroll
+        for (int i = 0; i < RowBlock<D>::N; ++i) zero.v[i] = i32x4{0, 0, 0, 0};
+        for (int hs = wave; hs < G; hs += NW) {
+            zero.store(o_buf, row_voff, head_soff(hs), q_row_bytes);
+            if (in && half == 0) p.lse[(size_t)(hk * G + hs) * p.n_q + row] = -INFINITY;
+        }
+        return;
+    }
+    const int kstart = h_lo & ~31;
+    const int nblk = (h_hi - kstart + 31) >> 5;          // 1 .. NB (the schedule marks the tile short only then)
+
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
+    const uint32_t stage = uniform(smem_base + 2 * HULL * ROWB + (uint32_t)wave * T::STAGE);
+    // Q rows of this wavefront's first two heads, in registers as whole rows; they pass through the
+    // staging tile into the MFMA operand layout when their turn comes
+    RowBlock<D> q_rows, q_next;
+    if (wave < G) q_rows.load(q_buf, row_voff, head_soff(wave), q_row_bytes);
+    q_next.load(q_buf, wave + NW < G ? row_voff : RowBlock<D>::kNowhere, head_soff(wave + NW), q_row_bytes);
+
+    const uint32_t kv_row = (uint32_t)p.hkv * D;
+    const uint32_t kv_bytes = ((uint32_t)p.t_kv * kv_row - (uint32_t)hk * D) * 2u;
+    BufRsrc krs, vrs;
+    krs.init(p.k + (size_t)hk * D, kv_bytes);
+    vrs.init(p.v + (size_t)hk * D, kv_bytes);
+    TileDma<D, 32 * NW, NW> dma;                          // wavefront w copies the 32-key block w
+    static_assert(TileDma<D, 32 * NW, NW>::PER * TileDma<D, 32 * NW, NW>::RPI == 32, "one 32-key block per wavefront");
+    dma.init(wave, lane, kv_row);
+    if (wave < nblk) {
+        dma.issue(krs, smem_base, kstart, wave);
+        dma.issue(vrs, smem_base + HULL * ROWB, kstart, wave);
+    }
+
+    const int lo = in ? p.row_lo[rc] : kPadLo;
+    const int hi = in ? p.row_hi[rc] : 0;
+    const bool real = hi > 0;
+
+    int kaddr[KS], vaddr[DB][2];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kaddr[ks] = l32 * ROWB + swz<CPR>(l32, ks * 2 + half) * 16;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int key = t * 8 + half * 4 + (j16 >> 2);
+            const int dch = db * 4 + gi * 2 + ((j16 & 3) >> 1);
+            vaddr[db][t] = smem_base + HULL * ROWB + key * ROWB + swz<CPR>(key, dch) * 16 + (j16 & 1) * 8;
+        }
+    const float cs = p.scale_log2e;
+
+    if (wave < G) q_rows.to_tile(stage, lane);
+    wait_vmem();
+    __syncthreads();              // the key window is in LDS; from here on the wavefronts do not meet again
+
+#pragma nounroll
+    for (int hs = wave; hs < G; hs += NW) {
+        const int h = hk * G + hs;
+        bf16x8 qf[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(stage + kaddr[ks]));
+
+        f32x16 s[NB];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[b][r] = -INFINITY;
+            if (b < nblk) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[b][r] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 a = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(smem_base + kaddr[ks] + b * 32 * ROWB));
+                    s[b] = mfma32(a, qf[ks], s[b]);
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = kstart + b * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                    s[b][r] = (key >= lo && key < hi) ? s[b][r] : -INFINITY;
+                    mx = fmaxf(mx, s[b][r]);
+                }
+            }
+        }
+        mx = fmaxf(mx, xhalf(mx));
+        const float mc = (mx == -INFINITY) ? 0.f : mx * cs;
+        f32x16 acc[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+        float l = 0.f;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (b < nblk) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float e = fast_exp2(fmaf(s[b][r], cs, -mc));
+                    s[b][r] = e;
+                    l += e;
+                }
+#pragma unroll
+                for (int cc = 0; cc < 2; ++cc) {
+                    const bf16x8 pf = pack8(s[b][8 * cc + 0], s[b][8 * cc + 1], s[b][8 * cc + 2], s[b][8 * cc + 3],
+                                            s[b][8 * cc + 4], s[b][8 * cc + 5], s[b][8 * cc + 6], s[b][8 * cc + 7]);
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        const int off = (b * 32 + cc * 16) * ROWB;
+                        const bf16x4 v0 = lds_read_tr4_at(vaddr[db][0] + off);
+                        const bf16x4 v1 = lds_read_tr4_at(vaddr[db][1] + off);
+                        acc[db] = mfma32(cat4(v0, v1), pf, acc[db]);
+                    }
+                }
+            }
+        }
+        const float lt = l + xhalf(l);
+        const bool live = real && (lt > 0.f);
+        const float inv = live ? 1.0f / lt : 0.f;
+        // O rows through the staging tile (its Q rows are in registers by now): written in the
+        // accumulator's layout, read back and stored as whole rows
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4)
+                *reinterpret_cast<WLB_LDS bf16x4*>((uintptr_t)(stage + l32 * ROWB + swz<CPR>(l32, db * 4 + r4) * 16 + half * 8)) =
+                    pack4(acc[db][r4 * 4 + 0] * inv, acc[db][r4 * 4 + 1] * inv, acc[db][r4 * 4 + 2] * inv, acc[db][r4 * 4 + 3] * inv);
+        RowBlock<D> o_rows;
+        o_rows.from_tile(stage, lane);
+        o_rows.store(o_buf, row_voff, head_soff(hs), q_row_bytes);
+        if (in && half == 0) p.lse[(size_t)h * p.n_q + row] = live ? mx * p.scale + __logf(lt) : -INFINITY;
+        wait_lds();                                 // the staging tile has been read back
+        q_next.to_tile(stage, lane);                // the next head's Q rows; the one after it starts its way
+        q_next.load(q_buf, hs + 2 * NW < G ? row_voff : RowBlock<D>::kNowhere, head_soff(hs + 2 * NW), q_row_bytes);
+    }
 }
 
 // Combines the partial results of a query tile that was cut at gang boundaries.  One workgroup per
@@ -409,8 +599,17 @@ wlb_status launch_fwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.partial = (float*)(ws + off_row_partial);
     p.n_q = d.n_q; p.t_kv = d.t_kv; p.hq = d.hq; p.hkv = d.hkv;
     p.n_groups = L.n_groups; p.n_tiles = L.n_fwd_tiles;
+    p.block_hull = (const int32_t*)(ws + L.off_block_hull);
+    p.tile_short = (const int32_t*)(ws + L.off_tile_short);
+    p.n_blocks32 = L.n_blocks32;
+    p.use_short = use_short_path(d, L) ? 1 : 0;
     p.scale = d.scale;
     p.scale_log2e = d.scale * 1.4426950408889634f;
+    if (p.use_short) {
+        const unsigned grid = 8u * (unsigned)((L.n_blocks32 + 7) / 8) * (unsigned)d.hkv;
+        if (d.head_dim == 128) fwd_short_kernel<128><<<grid, 256, 0, stream>>>(p);
+        else fwd_short_kernel<64><<<grid, 256, 0, stream>>>(p);
+    }
     if (use_row_gangs(d, L)) {
         const unsigned grid = (unsigned)L.row_gangs * (unsigned)(d.hq / d.hkv);
         if (d.head_dim == 128) {

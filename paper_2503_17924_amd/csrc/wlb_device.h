@@ -291,6 +291,53 @@ __device__ __forceinline__ void wait_vmem_le() {
 }
 
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+// every LDS access this wavefront has issued is complete (before a copy overwrites what was read)
+__device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xC07F); }    // lgkmcnt(0)
+
+// ------------------------------------------------------------------------------------------
+// Whole-row moves for the short-hull kernels: rows row0 .. row0+31 of one head of a
+// [n][heads][D] bf16 tensor travel between global memory, registers and a 32-row LDS tile
+// (swizzled like the K/V tiles) as complete rows -- every instruction covers RPI whole rows,
+// 64 lanes x 16 bytes -- through a bounds-checked buffer descriptor of the whole tensor, so rows
+// past its end load as zeros and are not stored, without a branch.
+typedef __amdgpu_buffer_rsrc_t buf_rsrc_t;
+__device__ __forceinline__ buf_rsrc_t make_buf(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+template <int D>
+struct RowBlock {
+    static constexpr int CPR = D / 8, ROWB = D * 2, RPI = 64 / CPR, N = 32 / RPI;
+    i32x4 v[N];
+    // lane's byte offset inside an instruction's rows, and the instructions' scalar offsets:
+    // row0 * row_bytes + head * ROWB + i * RPI * row_bytes
+    static __device__ __forceinline__ int lane_off(int lane, uint32_t row_bytes) { return (lane / CPR) * (int)row_bytes + (lane % CPR) * 16; }
+    // a lane offset past the end of any tensor: a load through it returns zeros and moves no data,
+    // which lets a prefetch be issued unconditionally ("nothing to fetch" costs no branch and leaves
+    // no value alive around a loop)
+    static constexpr int kNowhere = (int)0xfffffff0u;   // as an unsigned offset: beyond every tensor the library accepts (< 4 GiB)
+    __device__ __forceinline__ void load(buf_rsrc_t rs, int voff, uint32_t soff0, uint32_t row_bytes) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, (int)(soff0 + i * RPI * row_bytes), 0));
+    }
+    __device__ __forceinline__ void store(buf_rsrc_t rs, int voff, uint32_t soff0, uint32_t row_bytes) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((ext_vector_type(4))) unsigned, v[i]), rs, voff, (int)(soff0 + i * RPI * row_bytes), 0);
+    }
+    __device__ __forceinline__ void to_tile(uint32_t tile, int lane) const {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int r = i * RPI + lane / CPR, c = lane % CPR;
+            *reinterpret_cast<WLB_LDS i32x4*>((uintptr_t)(tile + r * ROWB + swz<CPR>(r, c) * 16)) = v[i];
+        }
+    }
+    __device__ __forceinline__ void from_tile(uint32_t tile, int lane) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int r = i * RPI + lane / CPR, c = lane % CPR;
+            v[i] = *reinterpret_cast<const WLB_LDS i32x4*>((uintptr_t)(tile + r * ROWB + swz<CPR>(r, c) * 16));
+        }
+    }
+};
 
 constexpr int kPadLo = 0x7fffffff;  // row_lo of a padding row (row_hi = 0): no key satisfies lo <= k < hi
 

@@ -18,6 +18,12 @@ constexpr int kBwdKeyTile = 128;  // keys per dK/dV work item
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 constexpr int kLists = 8;         // XCDs: workgroup b runs on XCD b % 8
+// Short-hull path of the forward and dQ kernels: a block of 32 rows whose visible keys, counted from
+// the 32-key boundary at or below the first, span at most kShortHullKeys keys is worked on by one
+// workgroup that holds those K/V rows in LDS for all query heads of the KV head.  A query tile
+// takes this path when each of its four blocks qualifies.
+constexpr int kShortBlockRows = 32;
+constexpr int kShortHullKeys = 96;
 #ifndef WLB_DKV_SPLIT
 #define WLB_DKV_SPLIT 6
 #endif
@@ -49,6 +55,9 @@ constexpr int kRowShareFirstFwd = 56, kRowShareFirstDq = 58;
 constexpr int kRowGangMaxItemsPerSlot = 3;
 constexpr int kRowGangMinUnitsPerSlot = 64;
 bool use_row_gangs(const wlb_attn_desc& d, const wlb_plan_layout& L);
+// whether this launch sends short-hull query tiles to the short-hull kernels (only in the
+// one-workgroup-per-item schedule; WLB_ATTN_NO_SHORT_PATH switches it off)
+bool use_short_path(const wlb_attn_desc& d, const wlb_plan_layout& L);
 // floats of one partial result of a query tile and head: 128 x D accumulator, then 128 row sums and
 // 128 reference exponents
 inline size_t row_partial_floats(int head_dim) { return (size_t)kFwdTileRows * head_dim + 2 * kFwdTileRows; }

@@ -35,7 +35,7 @@ wlb_status check_desc(const wlb_attn_desc* d) {
     const int64_t q_margin = 2LL * kBwdKeyTile * d->hq * d->head_dim, k_margin = 2LL * kBwdKeyTile * d->hkv * d->head_dim;
     if (qe * 2 + q_margin >= (1LL << 32) || ke * 2 + k_margin >= (1LL << 32))
         return fail(WLB_ERR_UNSUPPORTED, "attention: a tensor of 4 GiB or more is not supported");
-    if (d->flags & ~(WLB_ATTN_REUSE_PLAN | WLB_ATTN_BWD_SKIP_DELTA | WLB_ATTN_BWD_SKIP_DQ | WLB_ATTN_BWD_SKIP_DKV | WLB_ATTN_SCHEDULE_GANGS | WLB_ATTN_SCHEDULE_ITEMS)) return fail(WLB_ERR_INVALID_ARG, "attention: unknown flag bits 0x%x", d->flags);
+    if (d->flags & ~(WLB_ATTN_REUSE_PLAN | WLB_ATTN_BWD_SKIP_DELTA | WLB_ATTN_BWD_SKIP_DQ | WLB_ATTN_BWD_SKIP_DKV | WLB_ATTN_SCHEDULE_GANGS | WLB_ATTN_SCHEDULE_ITEMS | WLB_ATTN_NO_SHORT_PATH)) return fail(WLB_ERR_INVALID_ARG, "attention: unknown flag bits 0x%x", d->flags);
     return WLB_OK;
 }
 
@@ -65,6 +65,10 @@ bool use_row_gangs(const wlb_attn_desc& d, const wlb_plan_layout& L) {
     // (a tile sees about half its document: length / 128 key tiles), since the host does not see the mask
     const long long per_item = d.t_kv / d.n_docs / (2 * 64) + kRowItemOverhead;
     return items * per_item >= (long long)kRowGangMinUnitsPerSlot * slots;
+}
+
+bool use_short_path(const wlb_attn_desc& d, const wlb_plan_layout& L) {
+    return !(d.flags & WLB_ATTN_NO_SHORT_PATH) && !use_row_gangs(d, L);
 }
 
 size_t row_partial_bytes(const wlb_attn_desc& d, const wlb_plan_layout& L) {
@@ -99,6 +103,9 @@ void plan_layout(const wlb_attn_desc& d, wlb_plan_layout* L) {
     L->off_key_slot_base = take(sizeof(int32_t) * (L->n_key_tiles + 1));
     L->row_gangs = row_gangs(d.hq, d.hkv, compute_units());
     L->off_fwd_prefix = take(sizeof(int64_t) * (L->n_fwd_tiles + 1));
+    L->n_blocks32 = L->n_groups * (kGroupRows / kShortBlockRows);
+    L->off_block_hull = take(sizeof(int32_t) * 2 * L->n_blocks32);
+    L->off_tile_short = take(sizeof(int32_t) * L->n_fwd_tiles);
     L->plan_bytes = off;
 }
 
@@ -127,7 +134,7 @@ __global__ void __launch_bounds__(256) plan_rows_kernel(const int32_t* __restric
                                                         const int32_t* __restrict__ cu, int n_q, int t_kv,
                                                         int n_docs, int n_groups, int32_t* __restrict__ row_lo,
                                                         int32_t* __restrict__ row_hi, int32_t* __restrict__ group,
-                                                        int32_t* __restrict__ group_real) {
+                                                        int32_t* __restrict__ group_real, int32_t* __restrict__ block_hull) {
     const int lane = threadIdx.x & 63;
     const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (g >= n_groups) return;
@@ -149,8 +156,19 @@ __global__ void __launch_bounds__(256) plan_rows_kernel(const int32_t* __restric
         row_hi[i] = hi;
     }
     const bool real = hi > 0;
-    const int k_lo = wave_min(lo);                       // pads carry INT_MAX
-    const int k_hi = wave_max(hi);                       // pads carry 0
+    // hull of each half of the wavefront (a block of 32 rows), then of the whole group
+    int b_lo = lo, b_hi = hi;                            // pads carry INT_MAX / 0
+    for (int o = 16; o > 0; o >>= 1) {
+        b_lo = min(b_lo, __shfl_xor(b_lo, o));
+        b_hi = max(b_hi, __shfl_xor(b_hi, o));
+    }
+    if ((lane & 31) == 0) {
+        const int b = g * (kGroupRows / kShortBlockRows) + (lane >> 5);
+        block_hull[2 * b] = b_hi > 0 ? b_lo : 0;
+        block_hull[2 * b + 1] = b_hi;
+    }
+    const int k_lo = min(b_lo, __shfl_xor(b_lo, 32));
+    const int k_hi = max(b_hi, __shfl_xor(b_hi, 32));
     const int max_lo = wave_max(real ? lo : 0);
     const int min_hi = wave_min(real ? hi : kPadLo);
     if (lane == 0) {
@@ -165,8 +183,22 @@ __global__ void __launch_bounds__(256) plan_rows_kernel(const int32_t* __restric
 
 // cost of a forward tile = number of 64-key tiles between the hull's ends
 __device__ __forceinline__ void fwd_cost_of_tile(const int32_t* __restrict__ group, int n_groups, int n_tiles,
-                                                 int groups_per_tile, int32_t* __restrict__ cost, int t) {
+                                                 int groups_per_tile, int32_t* __restrict__ cost,
+                                                 const int32_t* __restrict__ block_hull, int32_t* __restrict__ tile_short, int t) {
     if (t >= n_tiles) return;
+    {
+        // short-hull tile: every block of 32 rows that has a real row sees keys inside one window of
+        // kShortHullKeys keys that starts at a multiple of 32
+        constexpr int per_tile = kFwdTileRows / kShortBlockRows, per_group = kGroupRows / kShortBlockRows;
+        bool is_short = true;
+        for (int j = 0; j < per_tile; ++j) {
+            const int b = t * per_tile + j;
+            if (b >= n_groups * per_group) break;
+            const int lo = block_hull[2 * b], hi = block_hull[2 * b + 1];
+            if (hi > lo && hi - (lo & ~31) > kShortHullKeys) is_short = false;
+        }
+        tile_short[t] = is_short ? 1 : 0;
+    }
     int k_lo = kPadLo, k_hi = 0;
     for (int j = 0; j < groups_per_tile; ++j) {
         const int g = t * groups_per_tile + j;
@@ -204,9 +236,12 @@ __device__ __forceinline__ void groups_of_key_tile(const int32_t* __restrict__ g
 __global__ void __launch_bounds__(256) plan_costs_kernel(const int32_t* __restrict__ group, int n_groups, int n_tiles,
                                                          int groups_per_tile, int32_t* __restrict__ fwd_cost,
                                                          int fwd_blocks, int n_key_tiles, int key_tile, int t_kv,
-                                                         int32_t* __restrict__ key_range, int32_t* __restrict__ key_cost) {
+                                                         int32_t* __restrict__ key_range, int32_t* __restrict__ key_cost,
+                                                         const int32_t* __restrict__ block_hull,
+                                                         int32_t* __restrict__ tile_short) {
     if ((int)blockIdx.x < fwd_blocks)
-        fwd_cost_of_tile(group, n_groups, n_tiles, groups_per_tile, fwd_cost, blockIdx.x * 256 + threadIdx.x);
+        fwd_cost_of_tile(group, n_groups, n_tiles, groups_per_tile, fwd_cost, block_hull, tile_short,
+                         blockIdx.x * 256 + threadIdx.x);
     else
         groups_of_key_tile(group, n_groups, n_key_tiles, key_tile, t_kv, key_range, key_cost,
                            ((int)blockIdx.x - fwd_blocks) * 4 + (threadIdx.x >> 6));
@@ -368,12 +403,14 @@ wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const i
     int32_t* key_range = (int32_t*)(ws + L.off_key_range);
     int32_t* key_cost = (int32_t*)(ws + off_key_cost(L));
     plan_rows_kernel<<<(L.n_groups + 3) / 4, 256, 0, stream>>>(q_idx, cu_seqlens_k, d.n_q, d.t_kv, d.n_docs,
-                                                                L.n_groups, row_lo, row_hi, group, group_real);
+                                                                L.n_groups, row_lo, row_hi, group, group_real,
+                                                                (int32_t*)(ws + L.off_block_hull));
     int32_t* key_ways = (int32_t*)(ws + L.off_key_ways);
     const int fwd_cost_blocks = (L.n_fwd_tiles + 255) / 256, key_tile_blocks = (L.n_key_tiles + 3) / 4;
     plan_costs_kernel<<<fwd_cost_blocks + key_tile_blocks, 256, 0, stream>>>(
         group, L.n_groups, L.n_fwd_tiles, kFwdTileRows / kGroupRows, fwd_cost, fwd_cost_blocks, L.n_key_tiles,
-        kBwdKeyTile, d.t_kv, key_range, key_cost);
+        kBwdKeyTile, d.t_kv, key_range, key_cost, (const int32_t*)(ws + L.off_block_hull),
+        (int32_t*)(ws + L.off_tile_short));
     const int fwd_order_blocks = (L.n_fwd_tiles + kOrderPerBlock - 1) / kOrderPerBlock;
     const int key_order_blocks = (L.n_key_tiles + kOrderPerBlock - 1) / kOrderPerBlock;
     plan_fwd_order_key_split_kernel<<<fwd_order_blocks + 1, 1024, 0, stream>>>(
