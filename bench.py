@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=2, help="workload index (2 = the 128K CP=8 config)")
+    ap.add_argument("--head-dim", type=int, default=0, choices=(0, 64, 128),
+                    help="run the workload's documents and head counts at another head dimension (profiling the D=64 kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-seq", action="store_true", help="skip the per-sequence sharding comparison")
     ap.add_argument("--no-others", action="store_true", help="skip the other workloads (profiling runs)")
@@ -297,6 +299,8 @@ def main():
                           "roofline": r["roofline"], "by_cp": r["by_cp"]}))
         return
     w = wl.config(args.config)
+    if args.head_dim and args.head_dim != w.head_dim:
+        w.head_dim, w.scale, w.name = args.head_dim, 1.0 / float(np.sqrt(args.head_dim)), f"{w.name}_d{args.head_dim}"
     if args.config == 3:
         raise SystemExit("config 3 (packing pool) is measured inside the default run; bench configs: 1, 2, 4, 5")
     D, hq = w.head_dim, w.hq
@@ -443,7 +447,7 @@ def main():
 
     # ---- the rest of the path's measurements, each a short run of its own
     others = None
-    if not args.no_others and args.config == 2:
+    if not args.no_others and args.config == 2 and not args.head_dim:
         others = {"small_document_regime": small_document_regime(B, torch, wl, 10, 3, device),
                   "c1_32k_gqa_cp1": other_config(B, torch, wl, 1, 1, 10, 3, device),
                   "c4_straggler_cp1": other_config(B, torch, wl, 4, 1, 3, 1, device),

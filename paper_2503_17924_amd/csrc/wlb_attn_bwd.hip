@@ -25,6 +25,7 @@
 #include <hip/hip_runtime.h>
 
 #include "wlb_device.h"
+#include <algorithm>
 #include <type_traits>
 
 #include "wlb_internal.h"
@@ -41,7 +42,7 @@ struct BwdParams {
     float* partial;
     RowSched sched;            // dQ: which query tiles, heads and key ranges a workgroup works on
     float* row_partial;        // dQ: partial results of the tiles cut at a gang boundary
-    const int32_t* block_hull; const int32_t* tile_short;   // short-hull path (see dq_short_kernel)
+    const int32_t* block_hull; const int32_t* tile_short;   // short-hull path (see dq_short_unit)
     int n_blocks32, use_short, delta_skips_short;
     int n_q, t_kv, hq, hkv, n_groups, n_tiles, n_key_tiles;
     float scale_log2e, scale;
@@ -51,27 +52,30 @@ struct BwdParams {
 template <int D>
 __global__ void __launch_bounds__(256) delta_kernel(const BwdParams p) {
     constexpr int LPR = D / 8;                       // lanes per (row, head)
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t rh = idx / LPR;                     // row * hq + head
-    const int c = (int)(idx % LPR);
-    size_t total = (size_t)p.n_q * p.hq;
-    // rows of short-hull tiles get delta and the LSE copy from dq_short_kernel
-    if (p.delta_skips_short && rh < total && p.tile_short[(rh / p.hq) / kFwdTileRows]) total = 0;
-    float acc = 0.f;
-    if (rh < total) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(p.d_o + rh * D + c * 8);
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(p.o + rh * D + c * 8);
+    const size_t total = (size_t)p.n_q * p.hq;
+    // a fixed number of workgroups walks the (row, head) pairs: rows of short-hull tiles, whose delta and
+    // LSE copy come from the short-hull dQ units, then cost a table lookup instead of a workgroup
+    for (size_t base = (size_t)blockIdx.x * 256; base < total * LPR; base += (size_t)gridDim.x * 256) {
+        const size_t idx = base + threadIdx.x;
+        const size_t rh = idx / LPR;                 // row * hq + head
+        const int c = (int)(idx % LPR);
+        const bool mine = rh < total && !(p.delta_skips_short && p.tile_short[(rh / p.hq) / kFwdTileRows]);
+        float acc = 0.f;
+        if (mine) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(p.d_o + rh * D + c * 8);
+            const bf16x8 b = *reinterpret_cast<const bf16x8*>(p.o + rh * D + c * 8);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc += (float)a[i] * (float)b[i];
-    }
+            for (int i = 0; i < 8; ++i) acc += (float)a[i] * (float)b[i];
+        }
 #pragma unroll
-    for (int o = LPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-    if (rh < total && c == 0) {
-        const int row = (int)(rh / p.hq), h = (int)(rh % p.hq);
-        const bool real = p.row_hi[row] > 0;
-        p.delta[(size_t)h * p.n_q + row] = real ? -acc : 0.f;
-        // LSE in log2 units for the dK/dV kernel; +inf makes every probability of a padding row 0
-        p.lse2[(size_t)h * p.n_q + row] = real ? p.lse[(size_t)h * p.n_q + row] * 1.4426950408889634f : INFINITY;
+        for (int o = LPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+        if (mine && c == 0) {
+            const int row = (int)(rh / p.hq), h = (int)(rh % p.hq);
+            const bool real = p.row_hi[row] > 0;
+            p.delta[(size_t)h * p.n_q + row] = real ? -acc : 0.f;
+            // LSE in log2 units for the dK/dV kernel; +inf makes every probability of a padding row 0
+            p.lse2[(size_t)h * p.n_q + row] = real ? p.lse[(size_t)h * p.n_q + row] * 1.4426950408889634f : INFINITY;
+        }
     }
 }
 
@@ -196,9 +200,12 @@ __device__ __forceinline__ void dq_piece(const BwdParams& p, char* smem, const R
         constexpr int kb_base = cur * TILEB, vb_base = (2 + cur) * TILEB;
         const bool partial = (j < fb) || (j >= fe);
         // S^T and dP^T of a 32-key block (two independent accumulation chains)
+        // At head_dim 64, where the kernel is bound by the vector ALU, the dP accumulation starts from -delta
+        // (the subtraction happens inside the first MFMA); at 128 that costs registers the kernel does not have.
+        constexpr bool kDeltaInMfma = D == 64;
         auto scores = [&](int kb, f32x16& s, f32x16& dp) __attribute__((always_inline)) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+            for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = kDeltaInMfma ? dl : 0.f; }
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 const bf16x8 ka = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(kb_base + naddr[ks] + kb * 32 * ROWB));
@@ -210,7 +217,7 @@ __device__ __forceinline__ void dq_piece(const BwdParams& p, char* smem, const R
         // dS^T = P^T o (dP^T - delta), in place of s; ls = the row's LSE, or +inf to switch the lane off
         auto grads = [&](f32x16& s, const f32x16& dp, float ls) __attribute__((always_inline)) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], cs, -ls)) * (dp[r] + dl);
+            for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], cs, -ls)) * (kDeltaInMfma ? dp[r] : dp[r] + dl);
         };
         // a block outside the fully visible range: rows that see none of its 32 keys (rows of another
         // document in the same wavefront) are switched off as whole lanes; the element-wise mask is
@@ -316,46 +323,26 @@ __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
     while (walk.next(p.sched, pc)) dq_piece<D>(p, smem, pc);
 }
 
-// The other schedule: one workgroup per (query tile in order, query head), heaviest first.
-template <int D>
-__global__ void __launch_bounds__(256, 2) dq_items_kernel(const BwdParams p) {
-    __shared__ __attribute__((aligned(1024))) char smem[4 * 64 * D * 2];
-    const int G = p.hq / p.hkv;
-    const int x = blockIdx.x & 7;
-    int y = blockIdx.x >> 3;
-    RowPiece pc;
-    pc.member = y % G; y /= G;
-    pc.hk = y % p.hkv;
-    const int rank = (y / p.hkv) * 8 + x;
-    if (rank >= p.n_tiles) return;
-    pc.tile = ld_const(p.sched.order + rank);
-    if (p.use_short && ld_const(p.tile_short + pc.tile)) return;     // dq_short_kernel's tile
-    pc.c = (int)(ld_const64(p.sched.prefix + rank + 1) - ld_const64(p.sched.prefix + rank));
-    pc.a = 0; pc.b = pc.c; pc.slot = -1;
-    dq_piece<D>(p, smem, pc);
-}
-
 // dQ of short-hull tiles, the counterpart of the forward's short-hull kernel (same workgroup shape,
 // same LDS layout: K window | V window | one staging tile per wavefront; see there).  A wavefront
-// works on one query head at a time; that head's rows of Q and dO reach it as whole rows -- held in
-// registers while the head before is computed -- and pass through the staging tile into the MFMA
-// operand layout.  All keys a row sees lie inside the window, so the wavefront has the row's whole
+// works on one query head at a time; that head's rows of Q and dO reach it as whole rows and pass
+// through the staging tile into the MFMA operand layout.  All keys a row sees lie inside the window, so the wavefront has the row's whole
 // P and dP and forms delta itself as sum_j P_ij dP_ij (equal to <dO_i, O_i> since O = P V), without
 // reading O: first pass per 32-key block S^T, dP^T, P and X = P o dP (both kept as bf16), then
 // dS^T = X - delta P and dQ^T += K^T dS^T.  delta (negated) and the log2-scaled LSE copy are left
 // for the dK/dV kernel, which runs after this one; the separate delta pass skips these rows.
 template <int D>
-__global__ void __launch_bounds__(256, 2) dq_short_kernel(const BwdParams p) {
+struct ShortDq {
+    static constexpr int NW = 4, ROWB = D * 2, HULL = kShortHullKeys, STAGE = kShortBlockRows * ROWB;
+    static constexpr int LDS_BYTES = 2 * HULL * ROWB + NW * STAGE;    // K window | V window | staging tiles
+};
+
+template <int D>
+__device__ __forceinline__ void dq_short_unit(const BwdParams& p, char* smem, int blk, int hk) {
     constexpr int NW = 4, KS = D / 16, DB = D / 32, CPR = D / 8, ROWB = D * 2;
     constexpr int HULL = kShortHullKeys, NB = HULL / 32, STAGE = kShortBlockRows * ROWB, RPI = 64 / CPR;
-    __shared__ __attribute__((aligned(1024))) char smem[2 * HULL * ROWB + NW * STAGE];
-
     const int G = p.hq / p.hkv;
-    const int per_xcd = (p.n_blocks32 + 7) / 8;
-    const int x = blockIdx.x & 7, jj = blockIdx.x >> 3;
-    const int blk = x * per_xcd + jj / p.hkv, hk = jj % p.hkv;
-    if (jj / p.hkv >= per_xcd || blk >= p.n_blocks32) return;
-    if (!ld_const(p.tile_short + blk / (kFwdTileRows / kShortBlockRows))) return;
+    __syncthreads();              // every wavefront has left the LDS of the unit before
 
     const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
@@ -394,13 +381,6 @@ __global__ void __launch_bounds__(256, 2) dq_short_kernel(const BwdParams p) {
     const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
     const uint32_t stage = uniform(smem_base + 2 * HULL * ROWB + (uint32_t)wave * STAGE);
 
-    // rows of the first head, in registers as whole rows
-    RowBlock<D> q_next, do_next;
-    if (wave < G) {
-        q_next.load(q_buf, row_voff, head_soff(wave), q_row_bytes);
-        do_next.load(do_buf, row_voff, head_soff(wave), q_row_bytes);
-    }
-
     const uint32_t kv_row = (uint32_t)p.hkv * D;
     const uint32_t kv_bytes = ((uint32_t)p.t_kv * kv_row - (uint32_t)hk * D) * 2u;
     BufRsrc krs, vrs;
@@ -416,9 +396,6 @@ __global__ void __launch_bounds__(256, 2) dq_short_kernel(const BwdParams p) {
     const int lo = in ? p.row_lo[rc] : kPadLo;
     const int hi = in ? p.row_hi[rc] : 0;
     const bool real = hi > 0;
-    float lsec = INFINITY;
-    if (wave < G && real) lsec = p.lse[(size_t)(hk * G + wave) * p.n_q + rc] * 1.4426950408889634f;
-
     int naddr[KS], taddr[DB][2];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) naddr[ks] = l32 * ROWB + swz<CPR>(l32, ks * 2 + half) * 16;
@@ -444,21 +421,26 @@ __global__ void __launch_bounds__(256, 2) dq_short_kernel(const BwdParams p) {
         }
     };
 
-    if (wave < G) q_next.to_tile(stage, lane);
     wait_vmem();
     __syncthreads();              // the key window is in LDS; the wavefronts do not meet again
 
 #pragma nounroll
     for (int hs = wave; hs < G; hs += NW) {
         const int h = hk * G + hs;
-        const bool more = hs + NW < G;
+        // this head's rows of Q and dO: whole rows into registers, then through the staging tile into the
+        // operand layout (eight wavefronts per compute unit cover each other's load latency)
         bf16x8 qf[KS], dof[KS];
-        rows_from_stage(qf);                      // Q rows, written to the staging tile above / at the end of the head before
-        wait_lds();
-        do_next.to_tile(stage, lane);
-        rows_from_stage(dof);
-        const float lse_cur = lsec;
-        if (more) lsec = real ? p.lse[(size_t)(h + NW) * p.n_q + rc] * 1.4426950408889634f : INFINITY;
+        {
+            RowBlock<D> q_rows, do_rows;
+            q_rows.load(q_buf, row_voff, head_soff(hs), q_row_bytes);
+            do_rows.load(do_buf, row_voff, head_soff(hs), q_row_bytes);
+            q_rows.to_tile(stage, lane);
+            rows_from_stage(qf);
+            wait_lds();
+            do_rows.to_tile(stage, lane);
+            rows_from_stage(dof);
+        }
+        const float lse_cur = real ? p.lse[(size_t)h * p.n_q + rc] * 1.4426950408889634f : INFINITY;
 
         // first pass: P and X = P o dP of every block (masked entries 0), delta = sum of X over the row
         bf16x8 pk[NB][2], xk[NB][2];
@@ -520,14 +502,6 @@ __global__ void __launch_bounds__(256, 2) dq_short_kernel(const BwdParams p) {
                 }
             }
         }
-        {
-            // the next head's rows start their way now that this head's operand registers are free; they have
-            // the second pass and the other wavefronts' work to arrive (after the last head: a load of nothing)
-            const int voff = more ? row_voff : RowBlock<D>::kNowhere;
-            q_next.load(q_buf, voff, head_soff(hs + NW), q_row_bytes);
-            do_next.load(do_buf, voff, head_soff(hs + NW), q_row_bytes);
-        }
-
         // second pass: dQ^T += K^T dS^T
         f32x16 acc[DB];
 #pragma unroll
@@ -560,8 +534,35 @@ __global__ void __launch_bounds__(256, 2) dq_short_kernel(const BwdParams p) {
         dq_rows.from_tile(stage, lane);
         dq_rows.store(dq_buf, row_voff, head_soff(hs), q_row_bytes);
         wait_lds();                                 // the staging tile has been read back
-        q_next.to_tile(stage, lane);
     }
+}
+
+// The other schedule: one workgroup per (query tile in order, query head), heaviest first.
+template <int D>
+__global__ void __launch_bounds__(256, 2) dq_items_kernel(const BwdParams p) {
+    constexpr int kLds = ShortDq<D>::LDS_BYTES > 4 * 64 * D * 2 ? ShortDq<D>::LDS_BYTES : 4 * 64 * D * 2;
+    __shared__ __attribute__((aligned(1024))) char smem[kLds];
+    const int G = p.hq / p.hkv;
+    const int x = blockIdx.x & 7;
+    int y = blockIdx.x >> 3;
+    RowPiece pc;
+    pc.member = y % G; y /= G;
+    pc.hk = y % p.hkv;
+    const int rank = (y / p.hkv) * 8 + x;
+    if (rank >= p.n_tiles) return;
+    pc.tile = ld_const(p.sched.order + rank);
+    if (p.use_short && ld_const(p.tile_short + pc.tile)) {
+        // a short-hull tile: its four blocks of 32 rows are units of their own (see dq_short_unit)
+        constexpr int per_tile = kFwdTileRows / kShortBlockRows;
+        for (int j = pc.member; j < per_tile; j += G) {
+            const int blk = pc.tile * per_tile + j;
+            if (blk < p.n_blocks32) dq_short_unit<D>(p, smem, blk, pc.hk);
+        }
+        return;
+    }
+    pc.c = (int)(ld_const64(p.sched.prefix + rank + 1) - ld_const64(p.sched.prefix + rank));
+    pc.a = 0; pc.b = pc.c; pc.slot = -1;
+    dq_piece<D>(p, smem, pc);
 }
 
 // Sums the partial dQ of a query tile that was cut at gang boundaries.  One workgroup per
@@ -1057,7 +1058,7 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.scale_log2e = d.scale * 1.4426950408889634f;
 
     const size_t n_lanes = (size_t)d.n_q * d.hq * (d.head_dim / 8);
-    const unsigned grid_delta = (unsigned)((n_lanes + 255) / 256);
+    const unsigned grid_delta = (unsigned)std::min<size_t>((n_lanes + 255) / 256, 8 * (size_t)compute_units());
     const unsigned grid_dq = (unsigned)L.row_gangs * (unsigned)(d.hq / d.hkv);
     const unsigned grid_dq_items = (unsigned)((L.n_fwd_tiles + 7) / 8) * 8u * (unsigned)d.hq;
     const bool gangs = use_row_gangs(d, L);
@@ -1070,34 +1071,32 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     // the short-hull dQ kernel forms delta for its own rows (and runs before dK/dV, which reads it);
     // when it does not run, the delta pass covers every row
     p.delta_skips_short = (p.use_short && do_dq) ? 1 : 0;
-    const unsigned grid_short = 8u * (unsigned)((L.n_blocks32 + 7) / 8) * (unsigned)d.hkv;
-    if (d.head_dim == 128) {
-        if (do_delta) delta_kernel<128><<<grid_delta, 256, 0, stream>>>(p);
-        if (do_dq && p.use_short) dq_short_kernel<128><<<grid_short, 256, 0, stream>>>(p);
-        if (do_dkv) {
-            dkv_kernel<128><<<grid_dkv, 512, 0, stream>>>(p);
-            dkv_fixup_kernel<128><<<grid_fix * kMergeSplit, 256, 0, stream>>>(p);
+    // Order: delta, then dK/dV (+ fix-up), then dQ (+ merge) -- except when short-hull units run inside the
+    // dQ launch: they leave delta for their rows, which dK/dV reads, so dQ goes first.
+    auto run = [&](auto dtag) {
+        constexpr int D = decltype(dtag)::value;
+        if (do_delta) delta_kernel<D><<<grid_delta, 256, 0, stream>>>(p);
+        auto dkv = [&] {
+            if (!do_dkv) return;
+            dkv_kernel<D><<<grid_dkv, 512, 0, stream>>>(p);
+            dkv_fixup_kernel<D><<<grid_fix * kMergeSplit, 256, 0, stream>>>(p);
+        };
+        if (gangs) {
+            dkv();
+            if (do_dq) {
+                dq_kernel<D><<<grid_dq, 256, 0, stream>>>(p);
+                dq_merge_kernel<D><<<grid_dq * kMergeSplit, 256, 0, stream>>>(p);
+            }
+        } else if (p.use_short) {
+            if (do_dq) dq_items_kernel<D><<<grid_dq_items, 256, 0, stream>>>(p);
+            dkv();
+        } else {
+            dkv();
+            if (do_dq) dq_items_kernel<D><<<grid_dq_items, 256, 0, stream>>>(p);
         }
-        if (do_dq && gangs) {
-            dq_kernel<128><<<grid_dq, 256, 0, stream>>>(p);
-            dq_merge_kernel<128><<<grid_dq * kMergeSplit, 256, 0, stream>>>(p);
-        } else if (do_dq) {
-            dq_items_kernel<128><<<grid_dq_items, 256, 0, stream>>>(p);
-        }
-    } else {
-        if (do_delta) delta_kernel<64><<<grid_delta, 256, 0, stream>>>(p);
-        if (do_dq && p.use_short) dq_short_kernel<64><<<grid_short, 256, 0, stream>>>(p);
-        if (do_dkv) {
-            dkv_kernel<64><<<grid_dkv, 512, 0, stream>>>(p);
-            dkv_fixup_kernel<64><<<grid_fix * kMergeSplit, 256, 0, stream>>>(p);
-        }
-        if (do_dq && gangs) {
-            dq_kernel<64><<<grid_dq, 256, 0, stream>>>(p);
-            dq_merge_kernel<64><<<grid_dq * kMergeSplit, 256, 0, stream>>>(p);
-        } else if (do_dq) {
-            dq_items_kernel<64><<<grid_dq_items, 256, 0, stream>>>(p);
-        }
-    }
+    };
+    if (d.head_dim == 128) run(std::integral_constant<int, 128>{});
+    else run(std::integral_constant<int, 64>{});
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(WLB_ERR_HIP, "backward launch: %s", hipGetErrorString(e));
     return WLB_OK;

@@ -27,7 +27,7 @@ struct FwdParams {
     const int32_t* row_lo; const int32_t* row_hi; const int32_t* group;
     RowSched sched;            // which query tiles, heads and key ranges a workgroup works on
     float* partial;            // partial results of the tiles cut at a gang boundary
-    const int32_t* block_hull; const int32_t* tile_short;   // short-hull path (see fwd_short_kernel)
+    const int32_t* block_hull; const int32_t* tile_short;   // short-hull path (see fwd_short_unit)
     int n_q, t_kv, hq, hkv, n_groups, n_tiles, n_blocks32, use_short;
     float scale_log2e, scale;
 };
@@ -325,36 +325,15 @@ __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
     while (walk.next(p.sched, pc)) fwd_piece<D>(p, smem, pc);
 }
 
-// The other schedule: one workgroup per (query tile in order, query head), dispatched heaviest
-// first.  With many tiles per workgroup slot the hardware's dynamic dispatch balances the load by
-// itself and adapts to whatever makes workgroups differ in speed; the gangs' fixed shares win when
-// there are only a few tiles per slot (long documents spread over many context-parallel ranks).
-template <int D>
-__global__ void __launch_bounds__(256, 2) fwd_items_kernel(const FwdParams p) {
-    __shared__ __attribute__((aligned(1024))) char smem[4 * 64 * D * 2];
-    const int G = p.hq / p.hkv;
-    const int x = blockIdx.x & 7;
-    int y = blockIdx.x >> 3;
-    RowPiece pc;
-    pc.member = y % G; y /= G;
-    pc.hk = y % p.hkv;
-    const int rank = (y / p.hkv) * 8 + x;
-    if (rank >= p.n_tiles) return;
-    pc.tile = ld_const(p.sched.order + rank);
-    if (p.use_short && ld_const(p.tile_short + pc.tile)) return;     // fwd_short_kernel's tile
-    pc.c = (int)(ld_const64(p.sched.prefix + rank + 1) - ld_const64(p.sched.prefix + rank));
-    pc.a = 0; pc.b = pc.c; pc.slot = -1;
-    fwd_piece<D>(p, smem, pc);
-}
-
 // Short-hull tiles (documents of a few dozen tokens, where a tile's rows see only the keys next to
-// them: the short-chunk case of paper Section 5.2).  There the general kernel is bound by latency:
-// per (tile, head) it fetches K/V, waits, and computes a handful of blocks.  Here a workgroup takes
-// one block of 32 rows and one KV head: it copies the (at most 96) keys the block sees into LDS
+// them: the short-chunk case of paper Section 5.2).  There the general piece of work is bound by
+// latency: per (tile, head) it fetches K/V, waits, and computes a handful of blocks.  A short-hull
+// unit is one block of 32 rows and one KV head, run by a workgroup of the one-workgroup-per-item
+// launch: it copies the (at most 96) keys the block sees into LDS
 // once -- K and V, in one shot -- and its four wavefronts then work independently, one query head
 // each at a time (heads w, w+4, ... of the KV head), with no further barrier.  Per head a wavefront
-// brings its 32 Q rows into a staging tile of its own by the same asynchronous copy (whole 256-byte
-// rows: loading the MFMA operand straight from global memory would touch 32 rows x 32 bytes per
+// loads its 32 Q rows as whole rows and passes them through a staging tile of its own into the MFMA
+// operand layout (loading the operand straight from global memory would touch 32 rows x 32 bytes per
 // instruction), computes the scores of the up to three 32-key blocks, the exact row maximum, the
 // exponentials and O^T += V^T P^T, and sends O through the staging tile so that it leaves in whole
 // rows as well.  Eight wavefronts per compute unit keep Q loads and O stores in flight; K/V
@@ -369,19 +348,11 @@ struct ShortTile {
 };
 
 template <int D>
-__global__ void __launch_bounds__(256, 2) fwd_short_kernel(const FwdParams p) {
+__device__ __forceinline__ void fwd_short_unit(const FwdParams& p, char* smem, int blk, int hk) {
     using T = ShortTile<D>;
     constexpr int NW = T::NW, KS = T::KS, DB = T::DB, CPR = T::CPR, ROWB = T::ROWB, HULL = T::HULL, NB = T::NB;
-    __shared__ __attribute__((aligned(1024))) char smem[T::LDS_BYTES];
-
     const int G = p.hq / p.hkv;
-    // workgroup -> (block of 32 rows, KV head); XCD x takes a contiguous range of blocks, so that
-    // neighbouring blocks, whose key windows overlap, read K/V through the same L2
-    const int per_xcd = (p.n_blocks32 + 7) / 8;
-    const int x = blockIdx.x & 7, jj = blockIdx.x >> 3;
-    const int blk = x * per_xcd + jj / p.hkv, hk = jj % p.hkv;
-    if (jj / p.hkv >= per_xcd || blk >= p.n_blocks32) return;
-    if (!ld_const(p.tile_short + blk / (kFwdTileRows / kShortBlockRows))) return;
+    __syncthreads();              // every wavefront has left the LDS of the unit before
 
     const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
@@ -414,12 +385,6 @@ __global__ void __launch_bounds__(256, 2) fwd_short_kernel(const FwdParams p) {
 
     const uint32_t smem_base = (uint32_t)(uintptr_t)(WLB_LDS char*)smem;
     const uint32_t stage = uniform(smem_base + 2 * HULL * ROWB + (uint32_t)wave * T::STAGE);
-    // Q rows of this wavefront's first two heads, in registers as whole rows; they pass through the
-    // staging tile into the MFMA operand layout when their turn comes
-    RowBlock<D> q_rows, q_next;
-    if (wave < G) q_rows.load(q_buf, row_voff, head_soff(wave), q_row_bytes);
-    q_next.load(q_buf, wave + NW < G ? row_voff : RowBlock<D>::kNowhere, head_soff(wave + NW), q_row_bytes);
-
     const uint32_t kv_row = (uint32_t)p.hkv * D;
     const uint32_t kv_bytes = ((uint32_t)p.t_kv * kv_row - (uint32_t)hk * D) * 2u;
     BufRsrc krs, vrs;
@@ -450,13 +415,19 @@ __global__ void __launch_bounds__(256, 2) fwd_short_kernel(const FwdParams p) {
         }
     const float cs = p.scale_log2e;
 
-    if (wave < G) q_rows.to_tile(stage, lane);
     wait_vmem();
     __syncthreads();              // the key window is in LDS; from here on the wavefronts do not meet again
 
 #pragma nounroll
     for (int hs = wave; hs < G; hs += NW) {
         const int h = hk * G + hs;
+        // this head's Q rows: whole rows into registers, then through the staging tile into the operand layout
+        // (eight wavefronts per compute unit cover each other's load latency)
+        {
+            RowBlock<D> q_rows;
+            q_rows.load(q_buf, row_voff, head_soff(hs), q_row_bytes);
+            q_rows.to_tile(stage, lane);
+        }
         bf16x8 qf[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const WLB_LDS bf16x8*>((uintptr_t)(stage + kaddr[ks]));
@@ -530,9 +501,39 @@ __global__ void __launch_bounds__(256, 2) fwd_short_kernel(const FwdParams p) {
         o_rows.store(o_buf, row_voff, head_soff(hs), q_row_bytes);
         if (in && half == 0) p.lse[(size_t)h * p.n_q + row] = live ? mx * p.scale + __logf(lt) : -INFINITY;
         wait_lds();                                 // the staging tile has been read back
-        q_next.to_tile(stage, lane);                // the next head's Q rows; the one after it starts its way
-        q_next.load(q_buf, hs + 2 * NW < G ? row_voff : RowBlock<D>::kNowhere, head_soff(hs + 2 * NW), q_row_bytes);
     }
+}
+
+// The other schedule: one workgroup per (query tile in order, query head), dispatched heaviest
+// first.  With many tiles per workgroup slot the hardware's dynamic dispatch balances the load by
+// itself and adapts to whatever makes workgroups differ in speed; the gangs' fixed shares win when
+// there are only a few tiles per slot (long documents spread over many context-parallel ranks).
+template <int D>
+__global__ void __launch_bounds__(256, 2) fwd_items_kernel(const FwdParams p) {
+    constexpr int kLds = ShortTile<D>::LDS_BYTES > 4 * 64 * D * 2 ? ShortTile<D>::LDS_BYTES : 4 * 64 * D * 2;
+    __shared__ __attribute__((aligned(1024))) char smem[kLds];
+    const int G = p.hq / p.hkv;
+    const int x = blockIdx.x & 7;
+    int y = blockIdx.x >> 3;
+    RowPiece pc;
+    pc.member = y % G; y /= G;
+    pc.hk = y % p.hkv;
+    const int rank = (y / p.hkv) * 8 + x;
+    if (rank >= p.n_tiles) return;
+    pc.tile = ld_const(p.sched.order + rank);
+    if (p.use_short && ld_const(p.tile_short + pc.tile)) {
+        // a short-hull tile: its four blocks of 32 rows are units of their own, each for all heads of the
+        // KV head; the tile's workgroups of this KV head share them out by member
+        constexpr int per_tile = kFwdTileRows / kShortBlockRows;
+        for (int j = pc.member; j < per_tile; j += G) {
+            const int blk = pc.tile * per_tile + j;
+            if (blk < p.n_blocks32) fwd_short_unit<D>(p, smem, blk, pc.hk);
+        }
+        return;
+    }
+    pc.c = (int)(ld_const64(p.sched.prefix + rank + 1) - ld_const64(p.sched.prefix + rank));
+    pc.a = 0; pc.b = pc.c; pc.slot = -1;
+    fwd_piece<D>(p, smem, pc);
 }
 
 // Combines the partial results of a query tile that was cut at gang boundaries.  One workgroup per
@@ -605,11 +606,6 @@ wlb_status launch_fwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.use_short = use_short_path(d, L) ? 1 : 0;
     p.scale = d.scale;
     p.scale_log2e = d.scale * 1.4426950408889634f;
-    if (p.use_short) {
-        const unsigned grid = 8u * (unsigned)((L.n_blocks32 + 7) / 8) * (unsigned)d.hkv;
-        if (d.head_dim == 128) fwd_short_kernel<128><<<grid, 256, 0, stream>>>(p);
-        else fwd_short_kernel<64><<<grid, 256, 0, stream>>>(p);
-    }
     if (use_row_gangs(d, L)) {
         const unsigned grid = (unsigned)L.row_gangs * (unsigned)(d.hq / d.hkv);
         if (d.head_dim == 128) {

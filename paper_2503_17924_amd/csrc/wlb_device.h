@@ -311,10 +311,6 @@ struct RowBlock {
     // lane's byte offset inside an instruction's rows, and the instructions' scalar offsets:
     // row0 * row_bytes + head * ROWB + i * RPI * row_bytes
     static __device__ __forceinline__ int lane_off(int lane, uint32_t row_bytes) { return (lane / CPR) * (int)row_bytes + (lane % CPR) * 16; }
-    // a lane offset past the end of any tensor: a load through it returns zeros and moves no data,
-    // which lets a prefetch be issued unconditionally ("nothing to fetch" costs no branch and leaves
-    // no value alive around a loop)
-    static constexpr int kNowhere = (int)0xfffffff0u;   // as an unsigned offset: beyond every tensor the library accepts (< 4 GiB)
     __device__ __forceinline__ void load(buf_rsrc_t rs, int voff, uint32_t soff0, uint32_t row_bytes) {
 #pragma unroll
         for (int i = 0; i < N; ++i) v[i] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, (int)(soff0 + i * RPI * row_bytes), 0));

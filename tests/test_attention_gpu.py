@@ -133,6 +133,60 @@ def test_gang_schedule_on_one_row():
         c.check_bwd(f" docs {docs}")
 
 
+SHORT_CASES = [
+    # docs, hq, hkv, d, cp: documents of a few dozen tokens, where whole query tiles take the short-hull path
+    (list(range(1, 65)) * 2, 16, 2, 128, 1),       # every length 1..64 twice, 8 heads per KV head (two per wavefront)
+    ([64] * 9 + [5], 4, 4, 128, 1),                # one head per KV head, last tile ragged
+    ([33, 1, 64, 17, 2, 48, 9, 60, 31] * 5, 6, 2, 64, 1),   # three heads per KV head, head_dim 64
+    ([40, 7, 64, 23, 12] * 9, 8, 1, 128, 2),       # sharded: pads, and key windows too wide for some tiles
+    ([64, 64, 300, 20, 20, 20, 64, 1000, 8, 8], 2, 1, 128, 1),   # short and long tiles in one launch
+]
+
+
+@pytest.mark.parametrize("docs,hq,hkv,d,cp", SHORT_CASES)
+def test_short_hull_path_matches_oracle(docs, hq, hkv, d, cp):
+    """Tiles whose 32-row blocks each see at most 96 keys run as short-hull units inside the
+    one-workgroup-per-item launches (forward, dQ with its own delta).  The schedule must mark them,
+    the results must match the oracle, and switching the path off must change nothing beyond rounding."""
+    import torch
+    w, tens = wl.small_case(90, docs, hq, hkv, d)
+    for r in sorted({0, cp - 1}):
+        sh = osh.shard(docs, cp, r, osh.PER_DOC_PADDED)
+        c = Case(tens, sh["q_idx"], sh["cu_seqlens_k"], hq, hkv, d, w.scale)
+        c.flags = B.ATTN_SCHEDULE_ITEMS
+        c.check_fwd(f" short rank {r}")
+        c.check_bwd(f" short rank {r}")
+        lay = B.wlb_attn_plan_layout(c.attn.desc)
+        ws = c.attn.workspace.cpu().numpy()
+        hull = ws[lay.off_block_hull:lay.off_block_hull + 8 * lay.n_blocks32].view(np.int32).reshape(-1, 2)
+        short = ws[lay.off_tile_short:lay.off_tile_short + 4 * lay.n_fwd_tiles].view(np.int32)
+        lo, hi = (ws[o:o + 4 * len(c.q_idx)].view(np.int32) for o in (lay.off_row_lo, lay.off_row_hi))
+        want_short = []
+        for t in range(lay.n_fwd_tiles):
+            ok = True
+            for b in range(4 * t, min(4 * t + 4, lay.n_blocks32)):
+                rows = slice(32 * b, min(32 * b + 32, len(c.q_idx)))
+                real = hi[rows] > 0
+                if real.any():
+                    assert hull[b, 0] == lo[rows][real].min() and hull[b, 1] == hi[rows][real].max()
+                    ok &= hull[b, 1] - (hull[b, 0] // 32) * 32 <= 96
+                else:
+                    assert hull[b, 1] <= hull[b, 0]
+            want_short.append(int(ok))
+        assert short.tolist() == want_short
+        if cp == 1:
+            assert sum(want_short) > 0, "this input is meant to exercise the short-hull path"
+        o1, l1 = c.run_fwd()
+        g1 = c.run_bwd()
+        c.flags = B.ATTN_SCHEDULE_ITEMS | B.ATTN_NO_SHORT_PATH
+        o2, l2 = c.run_fwd()
+        g2 = c.run_bwd()
+        real = c.q_idx >= 0
+        check_close("O short vs general", o1, o2, rows=real)
+        for name, a, b in zip(("dQ", "dK", "dV"), g1, g2):
+            check_close(f"{name} short vs general", a, b)
+
+
 ROW_ITEM_OVERHEAD = 6     # units of fixed cost per query tile in the forward / dQ work line
 DKV_SPLIT = 6             # a dK/dV item is at most 1/DKV_SPLIT of a compute unit's mean load
 DKV_MIN_ITEM_STAGES = 32  # items this short are not split further
