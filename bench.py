@@ -394,6 +394,30 @@ def main():
             "bwd_ms": [round(x, 3) for x in lat[:, 1]],
             "pairs_max_over_mean": float(max(s.pairs for s in ranks[m]) / np.mean([s.pairs for s in ranks[m]]))}
 
+    # ---- how evenly the gangs of the forward and dQ kernels finish (their workgroups leave start / end readings
+    # of the 100 MHz real-time counter in the workspace): spread of the gangs' end times relative to the kernel's
+    # duration, and mean end time of the first and the second half of the gangs (they get different shares)
+    gang_balance = None
+    lay0 = B.wlb_attn_plan_layout(main_states[0].attn.desc)
+    if lay0.uses_gangs:
+        G = hq // w.hkv
+        acc = {"fwd": [], "dq": []}
+        for st in main_states:
+            clk = B.gang_clocks(st.attn).astype(np.int64)
+            for k, name in enumerate(("fwd", "dq")):
+                t0 = clk[k, :, 0].min()
+                end = clk[k, :, 1] - t0
+                b = np.arange(len(end))
+                gang = ((b // 8) // G) * 8 + b % 8
+                gend = np.array([end[gang == g].max() for g in range(lay0.row_gangs)], dtype=np.float64)
+                half = lay0.row_gangs // 2
+                acc[name].append(((gend.max() - gend.min()) / gend.max(), gend[:half].mean() / gend.max(), gend[half:].mean() / gend.max()))
+        gang_balance = {name: {"end_time_spread_over_duration": round(float(np.mean([a[0] for a in v])), 4),
+                               "worst_rank_spread": round(float(np.max([a[0] for a in v])), 4),
+                               "mean_end_first_half_of_gangs": round(float(np.mean([a[1] for a in v])), 4),
+                               "mean_end_second_half_of_gangs": round(float(np.mean([a[2] for a in v])), 4)}
+                        for name, v in acc.items()}
+
     # ---- per-kernel timing on every rank: each kernel launched alone (the library's measurement flags),
     # timed with HIP events on the stream the library launches on (torch's current stream)
     def time_call(fn, reps=3):
@@ -434,6 +458,8 @@ def main():
     # the dense bf16 MFMA rate this GPU sustains (a kernel of nothing but MFMAs on register operands):
     # lower for random operand values -- what attention sees -- than for all-ones
     ceiling = {"all_ones": round(B.mfma_ceiling(False), 1), "random": round(B.mfma_ceiling(True), 1)}
+    # fp32 atomic-add rate (what a one-kernel backward would need for dQ): context for the 14*D executed flops
+    atomics = {"private_tiles_tb_per_s": round(B.atomic_add_rate(False), 3), "shared_tiles_tb_per_s": round(B.atomic_add_rate(True), 3)}
     roofline = {"bound": "mfma", "kernel": dominant + "_kernel", "achieved": round(tfl[dominant], 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl[dominant] / PEAK_BF16_TFLOPS, 4),
                 "measured_mfma_ceiling_tflops": ceiling,
@@ -469,7 +495,7 @@ def main():
                    "sharding": "per_document_padded", "useful_pairs": int(pairs)},
         "pct_of_bf16_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "pct_of_measured_mfma_ceiling_random_operands": round(100.0 * value / ceiling["random"], 2),
-        "per_rank_latency": per_rank,
+        "per_rank_latency": per_rank, "gang_balance": gang_balance, "atomic_add_rate": atomics,
         "host_us_per_step": {"pack": round(host_us_timed["pack"] / args.steps, 1),
                              "pack_what": "wlb_packer_step on one global batch (8 windows of 131072 tokens) of the config-3 pool",
                              "shard": round(host_us_timed["shard"] / args.steps, 1)},

@@ -241,18 +241,24 @@ typedef struct {
     size_t  off_key_ways;                /* int32 [n_key_tiles]: items per (key tile, KV head), by key tile */
     size_t  off_key_item_base;           /* int32 [n_key_tiles + 1]: first item of the tile of order rank r */
     size_t  off_key_slot_base;           /* int32 [n_key_tiles + 1]: first partial slot of the tile of rank r */
+    size_t  off_dkv_counters;            /* int32 [8]: dK/dV items handed out per XCD list; zero between launches */
     /* forward / dQ work: the query tiles in order, each repeated for every KV head, form one line of
        work measured in key tiles (plus a fixed per-tile cost); row_gangs gangs of hq/hkv workgroups
        take consecutive shares of it (the first half of the gangs, whose workgroups run faster, a
        somewhat larger one), so a tile cut by a share's end is finished by the next gang and the
        parts are merged from fp32 partial results */
     int32_t row_gangs;
+    int32_t uses_gangs;                  /* 1: forward and dQ of this desc (its flags included) run the gang schedule */
     size_t  off_fwd_prefix;              /* int64 [n_fwd_tiles + 1]: cost of the query tiles before order rank r */
     /* short-hull path: per block of 32 slots the hull {k_lo, k_hi} of the keys its real rows see (k_hi <= k_lo:
        no real row), and per query tile whether each of its blocks' hulls fits the short-hull kernels' LDS window */
     int32_t n_blocks32;
     size_t  off_block_hull;              /* int32 [n_blocks32][2] */
     size_t  off_tile_short;              /* int32 [n_fwd_tiles]: 1 = short-hull tile */
+    /* diagnostics of the gang schedule: each workgroup of the forward (k = 0) and dQ (k = 1) gang kernels leaves
+       the GPU's constant-rate real-time counter (100 MHz) at its start and at its end, so that a caller can see
+       how evenly the gangs finish: uint64 [2][row_gangs * hq / hkv][2], workgroup index as launched */
+    size_t  off_gang_clock;
     size_t  plan_bytes;
 } wlb_plan_layout;
 
@@ -342,6 +348,16 @@ wlb_status wlb_select_sharding(const int32_t* doc_len, int64_t n_docs, int32_t c
  * Errors: INVALID_ARG (null pointer, n_iter outside [1, 2^20]), HIP (launch failure).
  */
 wlb_status wlb_calib_mfma(int32_t random_operands, int32_t n_iter, float* sink, double* flops, void* stream);
+
+/* Measurement aid (not part of the method): one launch of a kernel that only adds 64 x 128 fp32 tiles into
+ * `buf` with device-scope atomic adds, one workgroup per compute unit, n_iter tiles each -- the traffic a
+ * single-kernel backward (Section 6.4 measures forward+backward) would produce for dQ.  shared = 0: every
+ * addition of a launch goes to a tile no other workgroup touches at that time (tiles are taken round-robin
+ * from buf); shared = 1: the workgroups walk the same few tiles.  buf: device, buf_bytes >= 32 KiB, holds
+ * floats that the launch increments.  *bytes_added (host) receives the bytes of fp32 data added; the caller
+ * times the launch on `stream`.  Asynchronous.  Errors: INVALID_ARG, HIP. */
+wlb_status wlb_calib_atomic_add(int32_t shared, int32_t n_iter, float* buf, size_t buf_bytes, double* bytes_added,
+                                void* stream);
 
 #ifdef __cplusplus
 }

@@ -33,7 +33,7 @@ STATUS_NAMES = {0: "WLB_OK", 1: "WLB_ERR_INVALID_ARG", 2: "WLB_ERR_BUFFER_TOO_SM
                 3: "WLB_ERR_UNSUPPORTED", 4: "WLB_ERR_HIP"}
 
 EXPORTS = ["wlb_last_error", "wlb_pack", "wlb_pack_optimal", "wlb_packer_create", "wlb_packer_destroy", "wlb_packer_step",
-           "wlb_packer_pending", "wlb_calib_mfma", "wlb_predict_latency", "wlb_select_sharding", "wlb_shard_size", "wlb_shard", "wlb_attn_workspace_size",
+           "wlb_packer_pending", "wlb_calib_mfma", "wlb_calib_atomic_add", "wlb_predict_latency", "wlb_select_sharding", "wlb_shard_size", "wlb_shard", "wlb_attn_workspace_size",
            "wlb_attn_plan", "wlb_attn_plan_layout", "wlb_attn_fwd", "wlb_attn_fwd_static", "wlb_attn_bwd"]
 
 
@@ -54,9 +54,10 @@ class PlanLayout(C.Structure):
                 ("off_row_lo", C.c_size_t), ("off_row_hi", C.c_size_t), ("off_group", C.c_size_t),
                 ("off_group_real", C.c_size_t), ("off_fwd_order", C.c_size_t), ("off_fwd_cost", C.c_size_t), ("off_key_order", C.c_size_t),
                 ("off_key_range", C.c_size_t), ("dkv_max_items", C.c_int32), ("dkv_max_partials", C.c_int32),
-                ("off_key_ways", C.c_size_t), ("off_key_item_base", C.c_size_t), ("off_key_slot_base", C.c_size_t),
-                ("row_gangs", C.c_int32), ("off_fwd_prefix", C.c_size_t),
+                ("off_key_ways", C.c_size_t), ("off_key_item_base", C.c_size_t), ("off_key_slot_base", C.c_size_t), ("off_dkv_counters", C.c_size_t),
+                ("row_gangs", C.c_int32), ("uses_gangs", C.c_int32), ("off_fwd_prefix", C.c_size_t),
                 ("n_blocks32", C.c_int32), ("off_block_hull", C.c_size_t), ("off_tile_short", C.c_size_t),
+                ("off_gang_clock", C.c_size_t),
                 ("plan_bytes", C.c_size_t)]
 
 
@@ -128,6 +129,26 @@ def mfma_ceiling(random_operands: bool, n_iter: int = 4000, reps: int = 8) -> fl
     e1.record()
     torch.cuda.synchronize()
     return flops.value * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+def atomic_add_rate(shared: bool, buf_mib: int = 256, n_iter: int = 200, reps: int = 3) -> float:
+    """TB/s of fp32 data added to device memory by atomics, measured with wlb_calib_atomic_add."""
+    import torch
+    buf = torch.zeros(buf_mib << 18, dtype=torch.float32, device="cuda")
+    done = C.c_double(0.0)
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def launch():
+        _check(lib().wlb_calib_atomic_add(C.c_int32(int(shared)), C.c_int32(n_iter), C.c_void_p(buf.data_ptr()),
+                                          C.c_size_t(buf.numel() * 4), C.byref(done), stream))
+    launch()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        launch()
+    e1.record()
+    torch.cuda.synchronize()
+    return done.value * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
 
 def wlb_pack_optimal(doc_len, n_microbatch: int, l_max: int, cost_a: int, cost_b: int, node_limit: int = 0):
@@ -369,6 +390,15 @@ class Attention:
         wlb_attn_bwd(desc, q, k, v, o, lse, d_o, self.q_idx, self.cu_k, dq, dk, dv, self.workspace)
         self.planned = True
         return dq, dk, dv
+
+
+def gang_clocks(attn: "Attention") -> np.ndarray:
+    """The start / end real-time counter values (100 MHz ticks) the gang kernels' workgroups left in the workspace
+    on their last launch: uint64 [2 (forward, dQ)][workgroups][2 (start, end)].  Reads the workspace (synchronises)."""
+    lay = wlb_attn_plan_layout(attn.desc)
+    n = lay.row_gangs * (attn.shape[3] // attn.shape[4])
+    raw = attn.workspace[lay.off_gang_clock:lay.off_gang_clock + 2 * n * 2 * 8].cpu().numpy()
+    return raw.view(np.uint64).reshape(2, n, 2)
 
 
 def bf16_bits_to_tensor(bits: np.ndarray, device="cuda:0"):

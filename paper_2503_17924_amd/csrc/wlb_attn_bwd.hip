@@ -39,10 +39,12 @@ struct BwdParams {
     const int32_t* row_lo; const int32_t* row_hi; const int32_t* group; const int32_t* group_real;
     const int32_t* key_order; const int32_t* key_range;
     const int32_t* key_ways; const int32_t* key_item_base; const int32_t* key_slot_base;
+    int32_t* dkv_counters;     // [8]: items of each XCD's list handed out so far (zero before every dK/dV launch)
     float* partial;
     RowSched sched;            // dQ: which query tiles, heads and key ranges a workgroup works on
     float* row_partial;        // dQ: partial results of the tiles cut at a gang boundary
     const int32_t* block_hull; const int32_t* tile_short;   // short-hull path (see dq_short_unit)
+    unsigned long long* gang_clock;   // [workgroup][2]: real-time counter at the start / end of dq_kernel's workgroup
     int n_blocks32, use_short, delta_skips_short;
     int n_q, t_kv, hq, hkv, n_groups, n_tiles, n_key_tiles;
     float scale_log2e, scale;
@@ -317,10 +319,15 @@ __device__ __forceinline__ void dq_piece(const BwdParams& p, char* smem, const R
 template <int D>
 __global__ void __launch_bounds__(256, 2) dq_kernel(const BwdParams p) {
     __shared__ __attribute__((aligned(1024))) char smem[4 * 64 * D * 2];   // K0 | K1 | V0 | V1
+    const unsigned long long t_start = wall_clock64();
     RowWalk walk;
     walk.start(p.sched, (int)blockIdx.x);
     RowPiece pc;
     while (walk.next(p.sched, pc)) dq_piece<D>(p, smem, pc);
+    if (threadIdx.x == 0) {
+        p.gang_clock[2 * blockIdx.x] = t_start;
+        p.gang_clock[2 * blockIdx.x + 1] = wall_clock64();
+    }
 }
 
 // dQ of short-hull tiles, the counterpart of the forward's short-hull kernel (same workgroup shape,
@@ -623,19 +630,37 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
     __shared__ __attribute__((aligned(256))) int small_s[NBUF][4][GR];       // per stage buffer: lse2 | delta | row_lo | row_hi
 
     const int G = p.hq / p.hkv;
-    // Work item blockIdx.x: tiles in order (heaviest item first), a tile's items consecutive:
-    // KV head major, head part minor.  Consecutive items run on consecutive XCDs, so the same head
-    // part of neighbouring tiles shares an XCD (and its L2 copy of the Q / dO tiles).
+    // Work items: tiles in order (heaviest item first), a tile's items consecutive: KV head major, head
+    // part minor.  The launch is one workgroup per compute unit, and each takes item after item until
+    // none is left.  Item i belongs to XCD i % 8 (workgroup b runs on XCD b % 8): the same head part of
+    // neighbouring tiles then shares an XCD and its L2 copy of the Q / dO tiles.  A workgroup takes its own
+    // XCD's items first, through one counter per XCD, and the other XCDs' once those are gone: the XCDs
+    // of one GPU differ in speed by several percent (the same ones are slower in every launch), and with
+    // one workgroup per item the hardware hands every XCD the same number of them.
+    __shared__ int s_item;
     const int n_items = ld_const(p.key_item_base + p.n_key_tiles);
-    if ((int)blockIdx.x >= n_items) return;
+  for (;;) {
+    __syncthreads();              // every wavefront has left the LDS of the item before, and has read s_item
+    if (threadIdx.x == 0) {
+        int it = -1;
+        for (int k = 0; k < kLists && it < 0; ++k) {
+            const int c = ((int)blockIdx.x + k) % kLists;
+            const int cand = atomicAdd(p.dkv_counters + c, 1) * kLists + c;
+            if (cand < n_items) it = cand;
+        }
+        s_item = it;
+    }
+    __syncthreads();
+    const int item = uniform(s_item);
+    if (item < 0) break;
     int r = 0;
     for (int hi = p.n_key_tiles; hi - r > 1;) {
         const int mid = (r + hi) >> 1;
-        if (ld_const(p.key_item_base + mid) <= (int)blockIdx.x) r = mid; else hi = mid;
+        if (ld_const(p.key_item_base + mid) <= item) r = mid; else hi = mid;
     }
     const int kt = ld_const(p.key_order + r);
     const int ways = ld_const(p.key_ways + kt);
-    const int j = (int)blockIdx.x - ld_const(p.key_item_base + r);
+    const int j = item - ld_const(p.key_item_base + r);
     const int hk = j / ways, part = j % ways;
     const int nh = G / ways;                 // query heads of this item: hk * G + part * nh + [0, nh)
     const int h_first = hk * G + part * nh;
@@ -990,6 +1015,7 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
                                                           acc[db][r4 * 4 + 2], acc[db][r4 * 4 + 3]};
             }
     }
+  }   // next item
 }
 
 // Sums the partial results of the key tiles that were split into several items.
@@ -997,6 +1023,8 @@ __global__ void __launch_bounds__(512) dkv_kernel(const BwdParams p) {
 template <int D>
 __global__ void __launch_bounds__(256) dkv_fixup_kernel(const BwdParams p) {
     constexpr int BNK = kBwdKeyTile;
+    // the item counters of the dK/dV launch that has just finished go back to zero for the next one
+    if (blockIdx.x == 0 && threadIdx.x < kLists) p.dkv_counters[threadIdx.x] = 0;
     const int job = (int)blockIdx.x / kMergeSplit, quarter = (int)blockIdx.x % kMergeSplit;
     const int hk = job % p.hkv, r = job / p.hkv;
     const int kt = p.key_order[r];
@@ -1043,6 +1071,7 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.key_ways = (const int32_t*)(ws + L.off_key_ways);
     p.key_item_base = (const int32_t*)(ws + L.off_key_item_base);
     p.key_slot_base = (const int32_t*)(ws + L.off_key_slot_base);
+    p.dkv_counters = (int32_t*)(ws + L.off_dkv_counters);
     p.partial = (float*)(ws + off_delta + 2 * align_up(sizeof(float) * (size_t)d.hq * d.n_q, 256));
     p.sched.prefix = (const long long*)(ws + L.off_fwd_prefix);
     p.sched.order = (const int32_t*)(ws + L.off_fwd_order);
@@ -1052,6 +1081,7 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.block_hull = (const int32_t*)(ws + L.off_block_hull);
     p.tile_short = (const int32_t*)(ws + L.off_tile_short);
     p.n_blocks32 = L.n_blocks32;
+    p.gang_clock = (unsigned long long*)(ws + L.off_gang_clock) + 2 * (size_t)L.row_gangs * (d.hq / d.hkv);
     p.n_q = d.n_q; p.t_kv = d.t_kv; p.hq = d.hq; p.hkv = d.hkv;
     p.n_groups = L.n_groups; p.n_tiles = L.n_fwd_tiles; p.n_key_tiles = L.n_key_tiles;
     p.scale = d.scale;
@@ -1062,7 +1092,8 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     const unsigned grid_dq = (unsigned)L.row_gangs * (unsigned)(d.hq / d.hkv);
     const unsigned grid_dq_items = (unsigned)((L.n_fwd_tiles + 7) / 8) * 8u * (unsigned)d.hq;
     const bool gangs = use_row_gangs(d, L);
-    const unsigned grid_dkv = (unsigned)L.dkv_max_items;         // items past the actual count exit at once
+    // one workgroup per compute unit, each taking item after item
+    const unsigned grid_dkv = (unsigned)std::min(L.dkv_max_items, compute_units());   // one workgroup per compute unit, each taking item after item
     const unsigned grid_fix = (unsigned)(L.n_key_tiles * d.hkv);
     const bool do_delta = !(d.flags & WLB_ATTN_BWD_SKIP_DELTA);
     const bool do_dq = !(d.flags & WLB_ATTN_BWD_SKIP_DQ);

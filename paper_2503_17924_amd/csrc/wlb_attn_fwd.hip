@@ -28,6 +28,7 @@ struct FwdParams {
     RowSched sched;            // which query tiles, heads and key ranges a workgroup works on
     float* partial;            // partial results of the tiles cut at a gang boundary
     const int32_t* block_hull; const int32_t* tile_short;   // short-hull path (see fwd_short_unit)
+    unsigned long long* gang_clock;   // [workgroup][2]: real-time counter at the start / end of a gang kernel's workgroup
     int n_q, t_kv, hq, hkv, n_groups, n_tiles, n_blocks32, use_short;
     float scale_log2e, scale;
 };
@@ -319,10 +320,15 @@ __device__ __forceinline__ void fwd_piece(const FwdParams& p, char* smem, const 
 template <int D>
 __global__ void __launch_bounds__(256, 2) fwd_kernel(const FwdParams p) {
     __shared__ __attribute__((aligned(1024))) char smem[4 * 64 * D * 2];   // K0 | K1 | V0 | V1
+    const unsigned long long t_start = wall_clock64();
     RowWalk walk;
     walk.start(p.sched, (int)blockIdx.x);
     RowPiece pc;
     while (walk.next(p.sched, pc)) fwd_piece<D>(p, smem, pc);
+    if (threadIdx.x == 0) {
+        p.gang_clock[2 * blockIdx.x] = t_start;
+        p.gang_clock[2 * blockIdx.x + 1] = wall_clock64();
+    }
 }
 
 // Short-hull tiles (documents of a few dozen tokens, where a tile's rows see only the keys next to
@@ -604,6 +610,7 @@ wlb_status launch_fwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.tile_short = (const int32_t*)(ws + L.off_tile_short);
     p.n_blocks32 = L.n_blocks32;
     p.use_short = use_short_path(d, L) ? 1 : 0;
+    p.gang_clock = (unsigned long long*)(ws + L.off_gang_clock);
     p.scale = d.scale;
     p.scale_log2e = d.scale * 1.4426950408889634f;
     if (use_row_gangs(d, L)) {

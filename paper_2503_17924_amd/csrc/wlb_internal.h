@@ -46,8 +46,11 @@ inline int row_gangs(int hq, int hkv, int cus) {
 // fixed cost of a query tile (loading Q, the first copies, the output) in units of one key tile's work
 constexpr int kRowItemOverhead = 6;
 // relative work share (percent) of a gang of the first half of a launch; a gang of the second half
-// gets the rest (measured optimum: forward 56, dQ 58)
-constexpr int kRowShareFirstFwd = 56, kRowShareFirstDq = 58;
+// gets the rest.  Set from the gangs' recorded end times (wlb_plan_layout: off_gang_clock): with these
+// shares the two halves end together on average; what remains is a spread between the XCDs of a GPU
+// (one XCD's gangs end up to 8 % later than another's, the same ones in every launch), which fixed
+// shares cannot know.
+constexpr int kRowShareFirstFwd = 57, kRowShareFirstDq = 57;
 // Which of the two forward / dQ schedules a launch uses: gangs with fixed shares when there are fewer
 // than kRowGangMaxItemsPerSlot (query tile, head) items per workgroup slot and an estimated
 // kRowGangMinUnitsPerSlot key tiles of work per slot, else one workgroup per item.  The

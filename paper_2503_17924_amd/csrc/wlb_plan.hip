@@ -101,11 +101,14 @@ void plan_layout(const wlb_attn_desc& d, wlb_plan_layout* L) {
     L->off_key_ways = take(sizeof(int32_t) * L->n_key_tiles);
     L->off_key_item_base = take(sizeof(int32_t) * (L->n_key_tiles + 1));
     L->off_key_slot_base = take(sizeof(int32_t) * (L->n_key_tiles + 1));
+    L->off_dkv_counters = take(sizeof(int32_t) * kLists);
     L->row_gangs = row_gangs(d.hq, d.hkv, compute_units());
+    L->uses_gangs = use_row_gangs(d, *L) ? 1 : 0;
     L->off_fwd_prefix = take(sizeof(int64_t) * (L->n_fwd_tiles + 1));
     L->n_blocks32 = L->n_groups * (kGroupRows / kShortBlockRows);
     L->off_block_hull = take(sizeof(int32_t) * 2 * L->n_blocks32);
     L->off_tile_short = take(sizeof(int32_t) * L->n_fwd_tiles);
+    L->off_gang_clock = take(sizeof(uint64_t) * 2 * 2 * (size_t)L->row_gangs * (d.hq / d.hkv));
     L->plan_bytes = off;
 }
 
@@ -309,8 +312,10 @@ __device__ __forceinline__ void key_split_block(const int32_t* __restrict__ key_
 // One workgroup.  Exclusive prefix sums, by order rank, of the tiles' item counts and partial slots.
 __global__ void __launch_bounds__(1024) plan_key_bases_kernel(const int32_t* __restrict__ key_order,
                                                               const int32_t* __restrict__ ways, int n_key_tiles, int hkv,
-                                                              int32_t* __restrict__ item_base, int32_t* __restrict__ slot_base) {
+                                                              int32_t* __restrict__ item_base, int32_t* __restrict__ slot_base,
+                                                              int32_t* __restrict__ dkv_counters) {
     __shared__ int s_items[1024], s_slots[1024];
+    if (threadIdx.x < kLists) dkv_counters[threadIdx.x] = 0;
     const int per = (n_key_tiles + 1023) / 1024;
     const int r0 = threadIdx.x * per, r1 = min(r0 + per, n_key_tiles);
     int items = 0, slots = 0;
@@ -420,7 +425,8 @@ wlb_status launch_plan(const wlb_attn_desc& d, const wlb_plan_layout& L, const i
         key_cost, L.n_key_tiles, key_order, key_order_blocks, fwd_order, fwd_cost, L.n_fwd_tiles,
         (long long*)(ws + L.off_fwd_prefix));
     plan_key_bases_kernel<<<1, 1024, 0, stream>>>(key_order, key_ways, L.n_key_tiles, d.hkv,
-                                                  (int32_t*)(ws + L.off_key_item_base), (int32_t*)(ws + L.off_key_slot_base));
+                                                  (int32_t*)(ws + L.off_key_item_base), (int32_t*)(ws + L.off_key_slot_base),
+                                                  (int32_t*)(ws + L.off_dkv_counters));
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(WLB_ERR_HIP, "plan launch: %s", hipGetErrorString(e));
     return WLB_OK;
