@@ -289,6 +289,12 @@ def main():
     B.lib()                       # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     device = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=device)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if args.tiny_tail:
         r = small_document_regime(B, torch, wl, args.steps, args.warmup, device)
         print(json.dumps({"metric": "HBM GB/s, small-document regime (schedule + attention fwd + bwd)", "value": r["value"],
@@ -349,12 +355,6 @@ def main():
                 e2.record()
                 record.append((e0, e1, e2))
 
-    if args.copy_calibration:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=device)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
 
     main_states = ranks[B.SHARD_PER_DOC_PADDED]
     for _ in range(args.warmup):

@@ -194,12 +194,18 @@ struct RowCut {
 };
 
 // XOR swizzle of the 16-byte chunks of an unpadded row-major LDS tile whose rows hold CPR
-// chunks: logical chunk cc of row r is stored at chunk swz(r, cc).  With 256-byte rows it
-// makes both access patterns of the kernels bank-conflict free: 16 rows x one chunk (b128
-// MFMA operand reads) and 4 rows x 4 consecutive chunks (transpose reads).
+// chunks: logical chunk cc of row r is stored at chunk swz(r, cc).  It makes both access patterns
+// of the kernels bank-conflict free: 16 rows x one chunk (b128 MFMA operand reads) and 4 rows x 4
+// consecutive chunks (transpose reads).  An LDS access covers 256 bytes per cycle.  With 256-byte
+// rows (head_dim 128) a row is one such line and the 16 rows of a read must land in 16 different
+// chunk positions: row bits 0-1 go to chunk bits 2-3 and row bits 2-3 to chunk bits 0-1.  With
+// 128-byte rows (head_dim 64) two rows share a line -- the row's lowest bit already selects the
+// half -- so row bits 1-3 take that part: bit 1 to chunk bit 2, bits 2-3 to chunk bits 0-1.
 template <int CPR>
 __host__ __device__ __forceinline__ constexpr int swz(int r, int cc) {
-    return cc ^ ((((r & 3) << 2) | ((r >> 2) & 3)) & (CPR - 1));
+    static_assert(CPR == 8 || CPR == 16, "rows of 128 or 256 bytes");
+    return CPR == 16 ? cc ^ (((r & 3) << 2) | ((r >> 2) & 3))
+                     : cc ^ ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
 }
 
 // Asynchronous global -> LDS copy of a tile of ROWS rows x D bf16 (rows contiguous in LDS,
