@@ -264,6 +264,18 @@ typedef struct {
 
 wlb_status wlb_attn_plan_layout(const wlb_attn_desc* desc, wlb_plan_layout* layout);
 
+/* Weights of the gang schedule's shares (host call, process-wide, takes effect with the next forward / backward
+ * call; set it while no call is being issued on another thread).  The gangs of a forward (kernel = 0) or dQ
+ * (kernel = 1) launch take shares of the work proportional to weights[half * 8 + xcd]: half = 0 for the first
+ * n_gangs / 2 gangs of the launch, 1 for the others; gang g runs on XCD g % 8.  The defaults give the first half
+ * a larger share (its workgroups are the older wavefronts of their SIMDs and advance faster) and treat the XCDs
+ * alike; the XCDs of one GPU differ in speed by several percent, so a caller may measure them -- run a uniform
+ * problem with WLB_ATTN_SCHEDULE_GANGS and read the gangs' clocks at off_gang_clock -- and pass weights
+ * proportional to the measured speeds.  Weights change where query tiles are cut, i.e. the rounding of the
+ * results, never their definition; with fixed weights results stay reproducible bit for bit.
+ * weights: host, 16 values in [1, 10^6], or NULL to restore the defaults.  Errors: INVALID_ARG. */
+wlb_status wlb_attn_set_gang_weights(int32_t kernel, const int32_t* weights);
+
 /* Forward.  Device pointers: q [n_q][hq][D], k, v [t_kv][hkv][D] (bf16), q_idx, cu_seqlens_k;
  * outputs o [n_q][hq][D] bf16 and lse [hq][n_q] float are overwritten.
  * Errors: INVALID_ARG (null pointer, bad desc), UNSUPPORTED (head_dim; Q or K of 4 GiB or more,

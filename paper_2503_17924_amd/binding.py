@@ -34,7 +34,7 @@ STATUS_NAMES = {0: "WLB_OK", 1: "WLB_ERR_INVALID_ARG", 2: "WLB_ERR_BUFFER_TOO_SM
 
 EXPORTS = ["wlb_last_error", "wlb_pack", "wlb_pack_optimal", "wlb_packer_create", "wlb_packer_destroy", "wlb_packer_step",
            "wlb_packer_pending", "wlb_calib_mfma", "wlb_calib_atomic_add", "wlb_predict_latency", "wlb_select_sharding", "wlb_shard_size", "wlb_shard", "wlb_attn_workspace_size",
-           "wlb_attn_plan", "wlb_attn_plan_layout", "wlb_attn_fwd", "wlb_attn_fwd_static", "wlb_attn_bwd"]
+           "wlb_attn_plan", "wlb_attn_plan_layout", "wlb_attn_set_gang_weights", "wlb_attn_fwd", "wlb_attn_fwd_static", "wlb_attn_bwd"]
 
 
 class WlbError(RuntimeError):
@@ -392,6 +392,15 @@ class Attention:
         return dq, dk, dv
 
 
+def wlb_attn_set_gang_weights(kernel: int, weights=None):
+    """weights: 16 integers [half of the launch][XCD], or None for the defaults."""
+    if weights is None:
+        _check(lib().wlb_attn_set_gang_weights(C.c_int32(kernel), None))
+    else:
+        w = _i32(np.asarray(weights).reshape(16))
+        _check(lib().wlb_attn_set_gang_weights(C.c_int32(kernel), _np_ptr(w, C.c_int32)))
+
+
 def gang_clocks(attn: "Attention") -> np.ndarray:
     """The start / end real-time counter values (100 MHz ticks) the gang kernels' workgroups left in the workspace
     on their last launch: uint64 [2 (forward, dQ)][workgroups][2 (start, end)].  Reads the workspace (synchronises)."""
@@ -399,6 +408,51 @@ def gang_clocks(attn: "Attention") -> np.ndarray:
     n = lay.row_gangs * (attn.shape[3] // attn.shape[4])
     raw = attn.workspace[lay.off_gang_clock:lay.off_gang_clock + 2 * n * 2 * 8].cpu().numpy()
     return raw.view(np.uint64).reshape(2, n, 2)
+
+
+def calibrate_gang_weights(hq: int = 8, hkv: int = 1, head_dim: int = 128, rounds: int = 2, device="cuda:0"):
+    """Measures how fast the gangs of each XCD and each half of a launch advance on this GPU -- a uniform,
+    unmasked problem under the gang schedule, the gangs' recorded clocks -- and sets the share weights of the
+    forward and dQ kernels in proportion (wlb_attn_set_gang_weights).  Returns the weights, [kernel][16].
+    Call it once per process; wlb_attn_set_gang_weights(k, None) restores the defaults."""
+    import torch
+    t, n_q = 32768, 16384
+    g = torch.Generator(device=device).manual_seed(7)
+    mk = lambda n, h: torch.randn((n, h, head_dim), device=device, generator=g, dtype=torch.float32).to(torch.bfloat16)
+    q, do, k, v = mk(n_q, hq), mk(n_q, hq), mk(t, hkv), mk(t, hkv)
+    attn = Attention(np.full(n_q, t - 1, dtype=np.int32), np.array([0, t], dtype=np.int32), t, hq, hkv, head_dim,
+                     1.0 / float(np.sqrt(head_dim)), device)
+    lay = wlb_attn_plan_layout(attn.desc)
+    group = hq // hkv
+    b = np.arange(lay.row_gangs * group)
+    gang = ((b // 8) // group) * 8 + b % 8
+    half_of = (np.arange(lay.row_gangs) >= lay.row_gangs // 2).astype(int)
+    weights = [None, None]
+    for kern in (0, 1):
+        wlb_attn_set_gang_weights(kern, None)
+    o, lse = attn.forward(q, k, v, extra_flags=ATTN_SCHEDULE_GANGS)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    for _ in range(rounds):
+        for _ in range(2):
+            attn.forward(q, k, v, o, lse, extra_flags=ATTN_SCHEDULE_GANGS)
+            attn.backward(q, k, v, o, lse, do, dq, dk, dv, extra_flags=ATTN_SCHEDULE_GANGS | ATTN_BWD_SKIP_DKV)
+        clk = gang_clocks(attn).astype(np.int64)
+        for kern in (0, 1):
+            end = clk[kern, :, 1] - clk[kern, :, 0].min()
+            gend = np.array([end[gang == i].max() for i in range(lay.row_gangs)], dtype=np.float64)
+            cur = np.asarray(weights[kern], dtype=np.float64).reshape(2, 8) if weights[kern] is not None else None
+            if cur is None:
+                first = 57.0
+                cur = np.array([[first] * 8, [100.0 - first] * 8])
+            new = np.zeros((2, 8))
+            for h in range(2):
+                for x in range(8):
+                    sel = (half_of == h) & (np.arange(lay.row_gangs) % 8 == x)
+                    new[h, x] = cur[h, x] / gend[sel].mean() if sel.any() else cur[h, x]
+            new = np.maximum(np.rint(new / new.mean() * 1000.0), 1).astype(np.int32)
+            weights[kern] = new.reshape(16)
+            wlb_attn_set_gang_weights(kern, weights[kern])
+    return [w.tolist() for w in weights]
 
 
 def bf16_bits_to_tensor(bits: np.ndarray, device="cuda:0"):

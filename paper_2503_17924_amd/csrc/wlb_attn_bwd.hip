@@ -1076,7 +1076,7 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.sched.prefix = (const long long*)(ws + L.off_fwd_prefix);
     p.sched.order = (const int32_t*)(ws + L.off_fwd_order);
     p.sched.n_tiles = L.n_fwd_tiles; p.sched.hkv = d.hkv; p.sched.G = d.hq / d.hkv; p.sched.n_gangs = L.row_gangs;
-    p.sched.w_first = kRowShareFirstDq; p.sched.w_second = 100 - kRowShareFirstDq;
+    gang_weights(1, p.sched.weight);
     p.row_partial = (float*)((char*)p.partial + dkv_partial_bytes(d, L));
     p.block_hull = (const int32_t*)(ws + L.off_block_hull);
     p.tile_short = (const int32_t*)(ws + L.off_tile_short);

@@ -602,7 +602,7 @@ wlb_status launch_fwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.sched.prefix = (const long long*)(ws + L.off_fwd_prefix);
     p.sched.order = (const int32_t*)(ws + L.off_fwd_order);
     p.sched.n_tiles = L.n_fwd_tiles; p.sched.hkv = d.hkv; p.sched.G = d.hq / d.hkv; p.sched.n_gangs = L.row_gangs;
-    p.sched.w_first = kRowShareFirstFwd; p.sched.w_second = 100 - kRowShareFirstFwd;
+    gang_weights(0, p.sched.weight);
     p.partial = (float*)(ws + off_row_partial);
     p.n_q = d.n_q; p.t_kv = d.t_kv; p.hq = d.hq; p.hkv = d.hkv;
     p.n_groups = L.n_groups; p.n_tiles = L.n_fwd_tiles;

@@ -91,9 +91,11 @@ __device__ __forceinline__ long long ld_const64(const long long* p) {
 // repeated for every KV head, form one line of work measured in key tiles (each tile's stretch
 // begins with a few units that stand for its fixed cost).  A launch has n_gangs gangs of G = hq / hkv workgroups (one per query head of a KV
 // head); the gangs take consecutive shares of the line, so a gang's load does not depend on the
-// tiles' sizes.  The shares of the first half of the gangs are larger than those of the second
-// half (w_first : w_second): with two workgroups per compute unit the workgroups of the first half
-// of the launch are the older wavefronts of their SIMDs, win issue arbitration and advance faster.  A tile cut by a share's end is continued by
+// tiles' sizes.  The shares are weighted: those of the first half of the gangs are larger than those
+// of the second half (with two workgroups per compute unit the workgroups of the first half of the
+// launch are the older wavefronts of their SIMDs, win issue arbitration and advance faster), and a
+// caller that has measured how fast each XCD of its GPU runs can weight them by XCD as well
+// (wlb_attn_set_gang_weights).  A tile cut by a share's end is continued by
 // the next gang; the pieces of such a tile leave fp32 partial results that a merge kernel
 // combines.  Workgroup b is member (b / 8) % G of gang ((b / 8) / G) * 8 + b % 8: consecutive
 // workgroups go to consecutive XCDs, so a gang's members share an XCD (and its L2 copy of K/V).
@@ -101,13 +103,23 @@ struct RowSched {
     const long long* prefix;   // [n_tiles + 1] cost of the query tiles before order rank r
     const int32_t* order;      // [n_tiles]
     int n_tiles, hkv, G, n_gangs;
-    int w_first, w_second;     // relative shares of a gang of the first / second half of the gangs
+    // relative share of a gang, by the half of the launch it belongs to and by its XCD (gang g runs on XCD
+    // g % 8): weight[0][x] for the first n_gangs / 2 gangs, weight[1][x] for the rest
+    int weight[2][8];
+    // sum of the weights of the gangs before g (indices fixed at compile time: the table stays in scalar registers)
+    __device__ __forceinline__ long long weight_before(int g) const {
+        const int g0 = g < n_gangs / 2 ? g : n_gangs / 2;      // of them, those in the first half
+        long long cum = 0;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int n0 = (g0 + 7 - x) >> 3, n = (g + 7 - x) >> 3;   // gangs i < g0 (i < g) with i % 8 == x
+            cum += (long long)n0 * weight[0][x] + (long long)(n - n0) * weight[1][x];
+        }
+        return cum;
+    }
     // first unit of gang g's share of a line of W units (g = n_gangs: W)
     __device__ __forceinline__ long long share_begin(long long W, int g) const {
-        const int half = n_gangs / 2;
-        const long long cum = g <= half ? (long long)g * w_first : (long long)half * w_first + (long long)(g - half) * w_second;
-        const long long tot = (long long)half * w_first + (long long)(n_gangs - half) * w_second;
-        return W * cum / tot;
+        return W * weight_before(g) / weight_before(n_gangs);
     }
 };
 struct RowPiece {

@@ -45,12 +45,14 @@ inline int row_gangs(int hq, int hkv, int cus) {
 }
 // fixed cost of a query tile (loading Q, the first copies, the output) in units of one key tile's work
 constexpr int kRowItemOverhead = 6;
-// relative work share (percent) of a gang of the first half of a launch; a gang of the second half
-// gets the rest.  Set from the gangs' recorded end times (wlb_plan_layout: off_gang_clock): with these
-// shares the two halves end together on average; what remains is a spread between the XCDs of a GPU
-// (one XCD's gangs end up to 8 % later than another's, the same ones in every launch), which fixed
-// shares cannot know.
+// Default relative work share (percent) of a gang of the first half of a launch; a gang of the second half
+// gets the rest.  Set from the gangs' recorded end times (wlb_plan_layout: off_gang_clock): with these shares
+// the two halves end together on average.  What remains is a spread between the XCDs of a GPU (one XCD's
+// gangs end several percent later than another's, the same ones in every launch), which differs from GPU to
+// GPU: wlb_attn_set_gang_weights takes weights measured on the GPU at hand.
 constexpr int kRowShareFirstFwd = 57, kRowShareFirstDq = 57;
+// the weights in force for kernel 0 (forward) / 1 (dQ): [half of the launch][XCD]
+void gang_weights(int kernel, int out[2][8]);
 // Which of the two forward / dQ schedules a launch uses: gangs with fixed shares when there are fewer
 // than kRowGangMaxItemsPerSlot (query tile, head) items per workgroup slot and an estimated
 // kRowGangMinUnitsPerSlot key tiles of work per slot, else one workgroup per item.  The

@@ -67,6 +67,18 @@ bool use_row_gangs(const wlb_attn_desc& d, const wlb_plan_layout& L) {
     return items * per_item >= (long long)kRowGangMinUnitsPerSlot * slots;
 }
 
+// gang share weights: process-wide, set by wlb_attn_set_gang_weights (0 = not set: the defaults)
+static int g_gang_weight[2][2][8];
+static std::mutex g_gang_weight_mutex;
+
+void gang_weights(int kernel, int out[2][8]) {
+    std::lock_guard<std::mutex> lock(g_gang_weight_mutex);
+    const int first = kernel == 0 ? kRowShareFirstFwd : kRowShareFirstDq;
+    for (int h = 0; h < 2; ++h)
+        for (int x = 0; x < 8; ++x)
+            out[h][x] = g_gang_weight[kernel][0][0] > 0 ? g_gang_weight[kernel][h][x] : (h == 0 ? first : 100 - first);
+}
+
 bool use_short_path(const wlb_attn_desc& d, const wlb_plan_layout& L) {
     return !(d.flags & WLB_ATTN_NO_SHORT_PATH) && !use_row_gangs(d, L);
 }
@@ -475,6 +487,17 @@ extern "C" wlb_status wlb_attn_workspace_size(const wlb_attn_desc* desc, size_t*
     plan_layout(*desc, &L);
     *fwd_bytes = L.plan_bytes + row_partial_bytes(*desc, L);
     *bwd_bytes = L.plan_bytes + delta_bytes(*desc) + dkv_partial_bytes(*desc, L) + row_partial_bytes(*desc, L);
+    return WLB_OK;
+}
+
+extern "C" wlb_status wlb_attn_set_gang_weights(int32_t kernel, const int32_t* weights) {
+    if (kernel != 0 && kernel != 1) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_set_gang_weights: kernel=%d (0 = forward, 1 = dQ)", kernel);
+    if (weights)
+        for (int i = 0; i < 16; ++i)
+            if (weights[i] < 1 || weights[i] > 1000000)
+                return fail(WLB_ERR_INVALID_ARG, "wlb_attn_set_gang_weights: weight %d = %d outside [1, 10^6]", i, weights[i]);
+    std::lock_guard<std::mutex> lock(g_gang_weight_mutex);
+    for (int i = 0; i < 16; ++i) g_gang_weight[kernel][i / 8][i % 8] = weights ? weights[i] : 0;
     return WLB_OK;
 }
 

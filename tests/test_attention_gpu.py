@@ -122,6 +122,31 @@ def test_both_row_schedules_match_oracle(flag, hq, hkv, d):
         c.check_bwd(f" cp {cp} rank {r}")
 
 
+def test_gang_share_weights_change_the_cuts_not_the_result():
+    """wlb_attn_set_gang_weights: very uneven weights (by half of the launch and by XCD) move the points where
+    query tiles are cut between gangs; the results still match the oracle, and the defaults come back."""
+    docs = [2600, 1, 37, 900, 130, 64, 700]
+    w, tens = wl.small_case(79, docs, 8, 1, 128)
+    sh = osh.shard(docs, 2, 1, osh.PER_DOC_PADDED)
+    c = Case(tens, sh["q_idx"], sh["cu_seqlens_k"], 8, 1, 128, w.scale)
+    c.flags = B.ATTN_SCHEDULE_GANGS
+    o0, _ = c.run_fwd()
+    try:
+        B.wlb_attn_set_gang_weights(0, [100, 5, 60, 1000, 7, 300, 90, 33, 11, 250, 40, 40, 900, 2, 75, 120])
+        B.wlb_attn_set_gang_weights(1, [3, 500, 60, 10, 700, 30, 90, 330, 110, 25, 400, 4, 90, 200, 75, 12])
+        c.check_fwd(" uneven weights")
+        c.check_bwd(" uneven weights")
+        with pytest.raises(B.WlbError):
+            B.wlb_attn_set_gang_weights(0, [0] * 16)
+        with pytest.raises(B.WlbError):
+            B.wlb_attn_set_gang_weights(2, [1] * 16)
+    finally:
+        B.wlb_attn_set_gang_weights(0, None)
+        B.wlb_attn_set_gang_weights(1, None)
+    o1, _ = c.run_fwd()
+    assert np.array_equal(o0, o1), "default weights restored: same cuts, same bits"
+
+
 def test_gang_schedule_on_one_row():
     """Degenerate work lines: a single query row, and fewer units of work than gangs."""
     for docs in ([1], [5, 1, 2]):
