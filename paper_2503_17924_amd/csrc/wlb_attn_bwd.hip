@@ -139,20 +139,13 @@ __device__ __forceinline__ void dq_piece(const BwdParams& p, char* smem, const R
     const int lo = in ? p.row_lo[rc] : kPadLo;
     const int hi = in ? p.row_hi[rc] : 0;
     const bool real = hi > 0;
-    // key tiles every real row of this wavefront sees in full: only outside [fb, fe) it masks
-    {
-        int mlo = real ? lo : 0, mhi = real ? hi : kPadLo;
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) {
-            mlo = max(mlo, __shfl_xor(mlo, o));
-            mhi = min(mhi, __shfl_xor(mhi, o));
-        }
-        fb = uniform((mlo + BN - 1) / BN);
-        fe = uniform(mhi / BN);
-        if (fe < fb) fe = fb;
-    }
+    // key tiles this wavefront needs no element-wise mask for: only outside [fb, fe) it masks.  Inside, the
+    // rows of the wavefront's first document see every key and the rows of later documents none.
+    bool other_doc;
+    unmasked_tiles<BN>(lo, hi, real, fb, fe, other_doc);
     // padding rows: zero operands and LSE = +inf make P, dS and dQ exactly 0
     const float lsec = real ? p.lse[(size_t)h * p.n_q + rc] * 1.4426950408889634f : INFINITY;
+    float lsec_unmasked = other_doc ? INFINITY : lsec;           // inside [fb, fe): +inf switches the lane off
     const float dl = real ? p.delta[(size_t)h * p.n_q + rc] : 0.f;
     bf16x8 qf[KS], dof[KS];
     {
@@ -257,11 +250,29 @@ __device__ __forceinline__ void dq_piece(const BwdParams& p, char* smem, const R
         // exponentials beside block 1's score MFMAs, block 1's beside block 0's dQ update.  The mask
         // (only on a document's diagonal or edge) is a branch between those straight-line regions.
         f32x16 s0, dp0, s1, dp1;
-        float ls0 = lsec, ls1 = lsec;
+        float ls0 = lsec_unmasked, ls1 = lsec_unmasked;
         bool em0 = false, em1 = false;
         if (partial) {
             classify(0, ls0, em0);
             classify(1, ls1, em1);
+            if (!em0 && !em1) {
+                // Every row sees all or none of the tile's second block.  That stays so up to the next edge of
+                // a row's interval (the end of a row that sees it, the start of one still to come): the key
+                // tiles from the next one up to that edge become the unmasked range, the rows that see
+                // nothing switched off.  A wavefront that holds rows of two chunks of one document (or of
+                // two documents) crosses the keys between them without classifying every block.
+                const int key1 = j * BN + 32;
+                const bool none = (key1 + 32 <= lo) || (key1 >= hi);
+                int edge = none ? (lo >= key1 + 32 ? lo : kPadLo) : hi;
+#pragma unroll
+                for (int o = 16; o > 0; o >>= 1) edge = min(edge, __shfl_xor(edge, o));
+                const int j_edge = uniform(edge / BN);
+                if (j_edge > j + 1) {
+                    fb = j + 1;
+                    fe = j_edge;
+                    lsec_unmasked = none ? INFINITY : lsec;
+                }
+            }
         }
         scores(0, s0, dp0);
         scores(1, s1, dp1);

@@ -89,20 +89,12 @@ __device__ __forceinline__ void fwd_piece(const FwdParams& p, char* smem, const 
     const int rc = in ? row : p.n_q - 1;
     const int lo = in ? p.row_lo[rc] : kPadLo;
     const int hi = in ? p.row_hi[rc] : 0;
-    // Key tiles every real row of this wavefront sees in full: only outside [fb, fe) does the
-    // wavefront mask (a tile of 128 rows that straddles a document boundary masks in the one
-    // wavefront that holds the boundary, not in all four).
-    {
-        int mlo = hi > 0 ? lo : 0, mhi = hi > 0 ? hi : kPadLo;
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) {
-            mlo = max(mlo, __shfl_xor(mlo, o));
-            mhi = min(mhi, __shfl_xor(mhi, o));
-        }
-        fb = uniform((mlo + BN - 1) / BN);
-        fe = uniform(mhi / BN);
-        if (fe < fb) fe = fb;
-    }
+    // Key tiles this wavefront needs no element-wise mask for: only outside [fb, fe) does it mask.  Inside,
+    // the rows of the wavefront's first document see every key; rows of later documents in the same
+    // wavefront (a tile that straddles a document boundary has one such wavefront) see none of them and
+    // stay switched off as whole lanes until the range ends (`parked`).
+    bool parked;
+    unmasked_tiles<BN>(lo, hi, hi > 0, fb, fe, parked);
     bf16x8 qf[KS];
     {
         const __bf16* qp = p.q + ((size_t)rc * p.hq + h) * D + half * 8;
@@ -159,7 +151,11 @@ __device__ __forceinline__ void fwd_piece(const FwdParams& p, char* smem, const 
     // every exponential below 2^kSlack and makes the rescaling of the accumulator a rare event.
     constexpr float kSlack = 8.0f;
     float mc = 0.f;                 // m * scale*log2(e), 0 while m is still -inf
-    float lim = -INFINITY;          // mc + kSlack: a block max (scaled) above this forces an update
+    // mc + kSlack: a block max (scaled) above this forces an update.  A parked lane sees no key yet: its
+    // limit is +inf so that the scores it computes meanwhile never ask for an update, and its bias (added
+    // to the reference of the exponentials) is +inf so that they contribute nothing.
+    float lim = parked ? INFINITY : -INFINITY;
+    float bias_base = parked ? INFINITY : 0.f;
     // rare path, outside the straight-line block: mask a block of a partial tile, recompute its max
     auto mask_block = [&](f32x16& s, int key0) __attribute__((always_inline)) {
 #pragma unroll
@@ -173,23 +169,51 @@ __device__ __forceinline__ void fwd_piece(const FwdParams& p, char* smem, const 
     // (rows of another document in the same wavefront) whole lanes are switched off; the element-wise
     // mask is left to the blocks a row's interval really cuts (diagonal, document edges)
     // (a lane is switched off by adding +inf to the reference its exponentials are taken against)
-    float bias_cur = 0.f, bias_next = 0.f;
+    // past the unmasked range the parked lanes take part again with the limit that belongs to their reference
+    auto unpark = [&]() __attribute__((always_inline)) {
+        lim = parked ? ((m == -INFINITY) ? -INFINITY : mc + kSlack) : lim;
+        parked = false;
+        bias_base = 0.f;
+    };
+    if (jb >= fe) unpark();
+    float bias_cur = bias_base, bias_next = bias_base;
     auto mask_next = [&](f32x16& s, int key0, float mx) __attribute__((always_inline)) {
+        if (key0 >= fe * BN) unpark();
         const bool none = (key0 + 32 <= lo) || (key0 >= hi);
         const bool all = (key0 >= lo) && (key0 + 32 <= hi);
-        if (__any(!(none || all))) return mask_block(s, key0);
+        if (__any(!(none || all))) {
+            bias_next = 0.f;
+            return mask_block(s, key0);
+        }
+        // Every row sees all or none of this block.  That stays so up to the next edge of a row's interval
+        // (the end of a row that sees the block, the start of one that is still to come): the key tiles
+        // from the next one up to that edge become the unmasked range, with the rows that see nothing
+        // parked.  A wavefront that holds rows of two chunks of one document (or of two documents)
+        // crosses the keys between them at full speed this way.
+        int edge = none ? (lo >= key0 + 32 ? lo : kPadLo) : hi;
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) edge = min(edge, __shfl_xor(edge, o));
+        const int j_next = key0 / BN + 1, j_edge = uniform(edge / BN);
+        if (j_edge > j_next) {
+            fb = uniform(j_next);
+            fe = j_edge;
+            parked = none;
+            bias_base = none ? INFINITY : 0.f;
+            lim = none ? INFINITY : lim;
+        }
         bias_next = none ? INFINITY : 0.f;
         return none ? -INFINITY : mx;
     };
     // rare path: move the reference up to the running max and rescale what has been accumulated
     auto move_reference = [&](float mx) __attribute__((always_inline)) {
+        mx = parked ? -INFINITY : mx;
         const float m_new = fmaxf(m, mx);
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = fast_exp2(fmaf(m, cs, -m_use * cs));     // m = -inf gives 0 (nothing accumulated yet)
         const float a2 = (m == -INFINITY) ? 0.f : alpha;
         m = m_new;
         mc = m_use * cs;
-        lim = (m_new == -INFINITY) ? -INFINITY : mc + kSlack;
+        lim = parked ? INFINITY : ((m_new == -INFINITY) ? -INFINITY : mc + kSlack);
         l *= a2;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -246,7 +270,7 @@ __device__ __forceinline__ void fwd_piece(const FwdParams& p, char* smem, const 
         }
         s_cur = s_next;
         bias_cur = bias_next;
-        bias_next = 0.f;
+        bias_next = bias_base;
     };
     auto tile_step = [&](int j, auto cur_tag) __attribute__((always_inline)) {
         constexpr int cur = decltype(cur_tag)::value;
@@ -254,8 +278,9 @@ __device__ __forceinline__ void fwd_piece(const FwdParams& p, char* smem, const 
             dma.issue(krs, tile_ptr(cur ^ 1), (j + 1) * BN + 32, wave);
             dma.issue(vrs, tile_ptr(2 + (cur ^ 1)), (j + 1) * BN, wave);
         }
-        const bool part0 = (j < fb) || (j >= fe), part1 = (j + 1 < fb) || (j + 1 >= fe);
+        const bool part0 = (j < fb) || (j >= fe);
         block_step(cur * TILEB, (2 + cur) * TILEB, j * BN + 32, part0);
+        const bool part1 = (j + 1 < fb) || (j + 1 >= fe);        // the first step may have set a new range
         block_step(cur * TILEB + 32 * ROWB, (2 + cur) * TILEB + 32 * ROWB, (j + 1) * BN, part1);
         wait_vmem();
         __syncthreads();

@@ -355,4 +355,28 @@ struct RowBlock {
 
 constexpr int kPadLo = 0x7fffffff;  // row_lo of a padding row (row_hi = 0): no key satisfies lo <= k < hi
 
+// Key tiles (of BN keys) a wavefront of 32 rows needs no element-wise mask for.  The rows are split by the
+// start of their key interval [lo, hi): the rows that share the smallest start (the first document in the
+// wavefront) see every key of the tiles [fb, fe); the other real rows (`other`: rows of later documents
+// that share the wavefront) see none of them and are switched off as whole lanes there.  A wavefront of one
+// document gets the range all its rows see in full and no lane with `other` set; neither does one whose
+// range is empty.  Both halves of the
+// wavefront hold the same 32 rows, so the reductions run over the 32 lanes of a half.
+template <int BN>
+__device__ __forceinline__ void unmasked_tiles(int lo, int hi, bool real, int& fb, int& fe, bool& other) {
+    int lo_min = real ? lo : kPadLo;
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) lo_min = min(lo_min, __shfl_xor(lo_min, o));
+    const bool first = real && lo == lo_min;
+    other = real && !first;
+    int end = first ? hi : (other ? lo : kPadLo);      // the range ends where a first-document row stops seeing keys
+#pragma unroll                                         // or another document's keys begin
+    for (int o = 16; o > 0; o >>= 1) end = min(end, __shfl_xor(end, o));
+    const int b = lo_min == kPadLo ? 0 : (lo_min + BN - 1) / BN;
+    const int e = end == kPadLo ? 0 : end / BN;
+    fb = __builtin_amdgcn_readfirstlane(b);
+    fe = __builtin_amdgcn_readfirstlane(e < b ? b : e);
+    if (fe == fb) other = false;       // no such tile: every block is classified on its own
+}
+
 }  // namespace wlb
