@@ -47,9 +47,9 @@ def parse():
     ap.add_argument("--config", type=int, default=2, help="workload index (2 = the 128K CP=8 config)")
     ap.add_argument("--head-dim", type=int, default=0, choices=(0, 64, 128),
                     help="run the workload's documents and head counts at another head dimension (profiling the D=64 kernels)")
-    ap.add_argument("--calibrate-gang-weights", action="store_true",
-                    help="measure this GPU's XCDs on a uniform problem first and weight the gang shares accordingly "
-                         "(measured: no gain on the 128K workload, whose per-XCD spread follows its memory traffic)")
+    ap.add_argument("--no-gang-calibration", action="store_true",
+                    help="keep the default share weights of the gang schedule instead of measuring this GPU's XCDs "
+                         "during warm-up (binding.calibrate_gang_weights: three rounds of two untimed steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-seq", action="store_true", help="skip the per-sequence sharding comparison")
     ap.add_argument("--no-others", action="store_true", help="skip the other workloads (profiling runs)")
@@ -314,12 +314,6 @@ def main():
         raise SystemExit("config 3 (packing pool) is measured inside the default run; bench configs: 1, 2, 4, 5")
     D, hq = w.head_dim, w.hq
 
-    # per-process calibration of the gang schedule's share weights on this GPU (uniform problem, recorded clocks)
-    gang_weights = None
-    probe = B.wlb_attn_plan_layout(B._desc(max(w.total_tokens // w.cp, 1), w.total_tokens, len(w.doc_len), hq, w.hkv, D, w.scale))
-    if probe.uses_gangs and args.calibrate_gang_weights:
-        gang_weights = B.calibrate_gang_weights(hq, w.hkv, D)
-
     t0 = time.time()
     tens = w.tensors()
     full = {n: B.bf16_bits_to_tensor(a, device) for n, a in tens.items()}
@@ -366,6 +360,12 @@ def main():
 
 
     main_states = ranks[B.SHARD_PER_DOC_PADDED]
+    # Part of the warm-up: the XCDs of one GPU run the forward and dQ kernels at speeds that differ by several
+    # percent, and the gang schedule can weight each XCD's share; the factors are measured on this workload's
+    # own launches (the gangs' recorded clocks) and then stay fixed for the process.
+    gang_factors = None
+    if not args.no_gang_calibration:
+        gang_factors = B.calibrate_gang_weights([st.attn for st in main_states], lambda: step(main_states))
     for _ in range(args.warmup):
         step(main_states)
     torch.cuda.synchronize()
@@ -505,7 +505,7 @@ def main():
         "pct_of_bf16_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "pct_of_measured_mfma_ceiling_random_operands": round(100.0 * value / ceiling["random"], 2),
         "per_rank_latency": per_rank, "gang_balance": gang_balance,
-        "gang_weights_measured_on_this_gpu": None if gang_weights is None else {"fwd": gang_weights[0], "dq": gang_weights[1]}, "atomic_add_rate": atomics,
+        "gang_xcd_speed_factors_measured_in_warmup": gang_factors, "atomic_add_rate": atomics,
         "host_us_per_step": {"pack": round(host_us_timed["pack"] / args.steps, 1),
                              "pack_what": "wlb_packer_step on one global batch (8 windows of 131072 tokens) of the config-3 pool",
                              "shard": round(host_us_timed["shard"] / args.steps, 1)},

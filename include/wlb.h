@@ -269,12 +269,17 @@ wlb_status wlb_attn_plan_layout(const wlb_attn_desc* desc, wlb_plan_layout* layo
  * (kernel = 1) launch take shares of the work proportional to weights[half * 8 + xcd]: half = 0 for the first
  * n_gangs / 2 gangs of the launch, 1 for the others; gang g runs on XCD g % 8.  The defaults give the first half
  * a larger share (its workgroups are the older wavefronts of their SIMDs and advance faster) and treat the XCDs
- * alike; the XCDs of one GPU differ in speed by several percent, so a caller may measure them -- run a uniform
- * problem with WLB_ATTN_SCHEDULE_GANGS and read the gangs' clocks at off_gang_clock -- and pass weights
- * proportional to the measured speeds.  Weights change where query tiles are cut, i.e. the rounding of the
+ * alike; the XCDs of one GPU differ in speed by several percent (which ones are slow differs from GPU to GPU),
+ * so a caller may measure them -- run its own problem, or any with WLB_ATTN_SCHEDULE_GANGS, read the gangs'
+ * clocks at off_gang_clock, and scale the weights of each XCD by mean end time / that XCD's end time; two or
+ * three rounds settle.  Weights change where query tiles are cut, i.e. the rounding of the
  * results, never their definition; with fixed weights results stay reproducible bit for bit.
  * weights: host, 16 values in [1, 10^6], or NULL to restore the defaults.  Errors: INVALID_ARG. */
 wlb_status wlb_attn_set_gang_weights(int32_t kernel, const int32_t* weights);
+
+/* The weights in force for `kernel` (the defaults if none were set): weights_out: host, 16 values, layout as above.
+ * Errors: INVALID_ARG. */
+wlb_status wlb_attn_get_gang_weights(int32_t kernel, int32_t* weights_out);
 
 /* Forward.  Device pointers: q [n_q][hq][D], k, v [t_kv][hkv][D] (bf16), q_idx, cu_seqlens_k;
  * outputs o [n_q][hq][D] bf16 and lse [hq][n_q] float are overwritten.

@@ -34,7 +34,7 @@ STATUS_NAMES = {0: "WLB_OK", 1: "WLB_ERR_INVALID_ARG", 2: "WLB_ERR_BUFFER_TOO_SM
 
 EXPORTS = ["wlb_last_error", "wlb_pack", "wlb_pack_optimal", "wlb_packer_create", "wlb_packer_destroy", "wlb_packer_step",
            "wlb_packer_pending", "wlb_calib_mfma", "wlb_calib_atomic_add", "wlb_predict_latency", "wlb_select_sharding", "wlb_shard_size", "wlb_shard", "wlb_attn_workspace_size",
-           "wlb_attn_plan", "wlb_attn_plan_layout", "wlb_attn_set_gang_weights", "wlb_attn_fwd", "wlb_attn_fwd_static", "wlb_attn_bwd"]
+           "wlb_attn_plan", "wlb_attn_plan_layout", "wlb_attn_set_gang_weights", "wlb_attn_get_gang_weights", "wlb_attn_fwd", "wlb_attn_fwd_static", "wlb_attn_bwd"]
 
 
 class WlbError(RuntimeError):
@@ -401,6 +401,13 @@ def wlb_attn_set_gang_weights(kernel: int, weights=None):
         _check(lib().wlb_attn_set_gang_weights(C.c_int32(kernel), _np_ptr(w, C.c_int32)))
 
 
+def wlb_attn_get_gang_weights(kernel: int) -> np.ndarray:
+    """The 16 weights in force for the forward (0) or dQ (1) gang kernel: [half of the launch][XCD]."""
+    out = np.zeros(16, dtype=np.int32)
+    _check(lib().wlb_attn_get_gang_weights(C.c_int32(kernel), _np_ptr(out, C.c_int32)))
+    return out
+
+
 def gang_clocks(attn: "Attention") -> np.ndarray:
     """The start / end real-time counter values (100 MHz ticks) the gang kernels' workgroups left in the workspace
     on their last launch: uint64 [2 (forward, dQ)][workgroups][2 (start, end)].  Reads the workspace (synchronises)."""
@@ -410,49 +417,50 @@ def gang_clocks(attn: "Attention") -> np.ndarray:
     return raw.view(np.uint64).reshape(2, n, 2)
 
 
-def calibrate_gang_weights(hq: int = 8, hkv: int = 1, head_dim: int = 128, rounds: int = 2, device="cuda:0"):
-    """Measures how fast the gangs of each XCD and each half of a launch advance on this GPU -- a uniform,
-    unmasked problem under the gang schedule, the gangs' recorded clocks -- and sets the share weights of the
-    forward and dQ kernels in proportion (wlb_attn_set_gang_weights).  Returns the weights, [kernel][16].
-    Call it once per process; wlb_attn_set_gang_weights(k, None) restores the defaults."""
+def calibrate_gang_weights(attns, launch, rounds: int = 3, extra_flags: int = 0):
+    """Sets the XCD part of the gang schedule's share weights from measurement on this GPU.
+
+    The XCDs of one GPU run the forward and dQ kernels at speeds that differ by several percent (the same
+    ones are slow in every launch, which ones differs from GPU to GPU), and a gang's workgroups all sit on
+    one XCD (gang g on XCD g % 8).  `attns` are Attention objects whose problems use the gang schedule and
+    `launch()` runs forward and backward of each of them once (the caller's own tensors; `extra_flags` are the
+    descriptor flags those calls add, e.g. a forced schedule).  Per
+    round: launch twice, read the gangs' recorded clocks, and scale each XCD's weight by mean end time /
+    its gangs' median end time; the split between the halves of a launch keeps its default.  The weights
+    hold for the process (wlb_attn_set_gang_weights(k, None) restores the defaults).  Returns
+    {"fwd": [8 factors], "dq": [8 factors]} (relative speeds, mean 1), or None if no problem uses gangs."""
     import torch
-    t, n_q = 32768, 16384
-    g = torch.Generator(device=device).manual_seed(7)
-    mk = lambda n, h: torch.randn((n, h, head_dim), device=device, generator=g, dtype=torch.float32).to(torch.bfloat16)
-    q, do, k, v = mk(n_q, hq), mk(n_q, hq), mk(t, hkv), mk(t, hkv)
-    attn = Attention(np.full(n_q, t - 1, dtype=np.int32), np.array([0, t], dtype=np.int32), t, hq, hkv, head_dim,
-                     1.0 / float(np.sqrt(head_dim)), device)
-    lay = wlb_attn_plan_layout(attn.desc)
-    group = hq // hkv
-    b = np.arange(lay.row_gangs * group)
-    gang = ((b // 8) // group) * 8 + b % 8
-    half_of = (np.arange(lay.row_gangs) >= lay.row_gangs // 2).astype(int)
-    weights = [None, None]
+    use = [a for a in attns if wlb_attn_plan_layout(_desc(*a.shape, flags=a.desc.flags | extra_flags)).uses_gangs]
+    if not use:
+        return None
+    factor = np.ones((2, 8))
+    default = []
     for kern in (0, 1):
         wlb_attn_set_gang_weights(kern, None)
-    o, lse = attn.forward(q, k, v, extra_flags=ATTN_SCHEDULE_GANGS)
-    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        default.append(wlb_attn_get_gang_weights(kern).astype(np.float64).reshape(2, 8))
     for _ in range(rounds):
-        for _ in range(2):
-            attn.forward(q, k, v, o, lse, extra_flags=ATTN_SCHEDULE_GANGS)
-            attn.backward(q, k, v, o, lse, do, dq, dk, dv, extra_flags=ATTN_SCHEDULE_GANGS | ATTN_BWD_SKIP_DKV)
-        clk = gang_clocks(attn).astype(np.int64)
+        launch()
+        launch()
+        torch.cuda.synchronize()
+        ends = np.zeros((2, 8))
+        for a in use:
+            lay = wlb_attn_plan_layout(a.desc)
+            group = a.shape[3] // a.shape[4]
+            b = np.arange(lay.row_gangs * group)
+            gang = ((b // 8) // group) * 8 + b % 8
+            clk = gang_clocks(a).astype(np.int64)
+            for kern in (0, 1):
+                end = clk[kern, :, 1] - clk[kern, :, 0].min()
+                gend = np.array([end[gang == i].max() for i in range(lay.row_gangs)], dtype=np.float64)
+                xcd = np.arange(lay.row_gangs) % 8
+                per = np.array([np.median(gend[xcd == x]) if (xcd == x).any() else gend.mean() for x in range(8)])
+                ends[kern] += per / per.mean() / len(use)
+        factor = factor / ends
+        factor = np.clip(factor / factor.mean(axis=1, keepdims=True), 0.8, 1.25)
         for kern in (0, 1):
-            end = clk[kern, :, 1] - clk[kern, :, 0].min()
-            gend = np.array([end[gang == i].max() for i in range(lay.row_gangs)], dtype=np.float64)
-            cur = np.asarray(weights[kern], dtype=np.float64).reshape(2, 8) if weights[kern] is not None else None
-            if cur is None:
-                first = 57.0
-                cur = np.array([[first] * 8, [100.0 - first] * 8])
-            new = np.zeros((2, 8))
-            for h in range(2):
-                for x in range(8):
-                    sel = (half_of == h) & (np.arange(lay.row_gangs) % 8 == x)
-                    new[h, x] = cur[h, x] / gend[sel].mean() if sel.any() else cur[h, x]
-            new = np.maximum(np.rint(new / new.mean() * 1000.0), 1).astype(np.int32)
-            weights[kern] = new.reshape(16)
-            wlb_attn_set_gang_weights(kern, weights[kern])
-    return [w.tolist() for w in weights]
+            w = default[kern] * factor[kern][None, :] * 10.0
+            wlb_attn_set_gang_weights(kern, np.maximum(np.rint(w), 1).astype(np.int32).reshape(16))
+    return {"fwd": [round(float(x), 4) for x in factor[0]], "dq": [round(float(x), 4) for x in factor[1]]}
 
 
 def bf16_bits_to_tensor(bits: np.ndarray, device="cuda:0"):

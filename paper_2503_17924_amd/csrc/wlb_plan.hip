@@ -501,6 +501,15 @@ extern "C" wlb_status wlb_attn_set_gang_weights(int32_t kernel, const int32_t* w
     return WLB_OK;
 }
 
+extern "C" wlb_status wlb_attn_get_gang_weights(int32_t kernel, int32_t* weights_out) {
+    if (kernel < 0 || kernel > 1) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_get_gang_weights: kernel %d (0 = forward, 1 = dQ)", kernel);
+    if (!weights_out) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_get_gang_weights: null output");
+    int w[2][8];
+    gang_weights(kernel, w);
+    for (int i = 0; i < 16; ++i) weights_out[i] = w[i / 8][i % 8];
+    return WLB_OK;
+}
+
 extern "C" wlb_status wlb_attn_plan_layout(const wlb_attn_desc* desc, wlb_plan_layout* layout) {
     if (wlb_status st = check_desc(desc)) return st;
     if (!layout) return fail(WLB_ERR_INVALID_ARG, "wlb_attn_plan_layout: null output");

@@ -147,6 +147,38 @@ def test_gang_share_weights_change_the_cuts_not_the_result():
     assert np.array_equal(o0, o1), "default weights restored: same cuts, same bits"
 
 
+def test_gang_weights_calibrated_from_the_clocks_keep_the_result():
+    """binding.calibrate_gang_weights: XCD factors measured from the gangs' recorded clocks on the caller's own
+    launches; positive weights in the documented range result, the halves keep their default ratio, and forward
+    and backward still match the oracle."""
+    docs = [3000, 5, 1200, 64, 333]
+    w, tens = wl.small_case(83, docs, 8, 2, 128)
+    sh = osh.shard(docs, 1, 0, osh.PER_DOC_PADDED)
+    c = Case(tens, sh["q_idx"], sh["cu_seqlens_k"], 8, 2, 128, w.scale)
+    c.flags = B.ATTN_SCHEDULE_GANGS
+    default = [B.wlb_attn_get_gang_weights(k).copy() for k in (0, 1)]
+    try:
+        def launch():
+            c.run_fwd()
+            c.run_bwd()
+        factors = B.calibrate_gang_weights([c.attn], launch, rounds=2, extra_flags=B.ATTN_SCHEDULE_GANGS)
+        assert factors is not None and len(factors["fwd"]) == 8 and len(factors["dq"]) == 8
+        for k, name in enumerate(("fwd", "dq")):
+            got = B.wlb_attn_get_gang_weights(k).astype(np.float64).reshape(2, 8)
+            assert (got >= 1).all() and (got <= 1e6).all()
+            f = np.asarray(factors[name])
+            assert (f >= 0.8).all() and (f <= 1.25).all()
+            want = default[k].astype(np.float64).reshape(2, 8) * f[None, :] * 10.0
+            assert np.abs(got - want).max() <= 0.51
+        c.check_fwd(" calibrated weights")
+        c.check_bwd(" calibrated weights")
+        assert B.calibrate_gang_weights([c.attn], launch) is None, "without the flag this problem does not use gangs"
+    finally:
+        B.wlb_attn_set_gang_weights(0, None)
+        B.wlb_attn_set_gang_weights(1, None)
+    assert all(np.array_equal(B.wlb_attn_get_gang_weights(k), default[k]) for k in (0, 1))
+
+
 def test_gang_schedule_on_one_row():
     """Degenerate work lines: a single query row, and fewer units of work than gangs."""
     for docs in ([1], [5, 1, 2]):
