@@ -14,6 +14,10 @@ per-sequence sharding, the CPU oracle timed on a bounded sample of the same work
 "other_workloads" -- the remaining measurements of the path: the other configurations' rates, the
 small-document regime as HBM GB/s with its own roofline record, and the measured micro-batch
 latency imbalance of fixed against workload-balanced packing.
+
+During warm-up the share weights of the gang schedule are calibrated to the speeds of this GPU's XCDs
+(binding.calibrate_gang_weights; --no-gang-calibration keeps the defaults).  With WLB_TRACE=1 in the
+environment every rank's schedule (work-item costs, shares, splits) is described on stderr.
 """
 from __future__ import annotations
 
@@ -360,6 +364,11 @@ def main():
 
 
     main_states = ranks[B.SHARD_PER_DOC_PADDED]
+    if os.environ.get("WLB_TRACE") == "1":
+        # the schedule of every rank (work-item costs, shares, splits) on stderr, for looking at it by eye
+        for st in main_states:
+            st.attn.plan()
+            print(B.plan_report(st.attn, f"{w.name} rank {st.rank}"), file=sys.stderr)
     # Part of the warm-up: the XCDs of one GPU run the forward and dQ kernels at speeds that differ by several
     # percent, and the gang schedule can weight each XCD's share; the factors are measured on this workload's
     # own launches (the gangs' recorded clocks) and then stay fixed for the process.

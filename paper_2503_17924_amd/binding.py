@@ -401,6 +401,62 @@ def wlb_attn_set_gang_weights(kernel: int, weights=None):
         _check(lib().wlb_attn_set_gang_weights(C.c_int32(kernel), _np_ptr(w, C.c_int32)))
 
 
+def plan_tables(attn: "Attention") -> dict:
+    """The schedule the last wlb_attn_plan / forward / backward call of `attn` left in its workspace, as host
+    arrays (reads the workspace: synchronises).  Keys: row_lo, row_hi [n_q]; group [n_groups][4] (hull and fully
+    visible key range of each 64-row group); fwd_cost [n_fwd_tiles] (64-key tiles a query tile visits), fwd_order
+    (heaviest first), fwd_prefix [n_fwd_tiles + 1] (running cost in that order, fixed cost per tile included);
+    tile_short; key_range [n_key_tiles][2] (row groups a key tile is visible to), key_ways (items a key tile is
+    split into), key_order, key_item_base; layout (the PlanLayout)."""
+    lay = wlb_attn_plan_layout(attn.desc)
+    ws = attn.workspace[:lay.plan_bytes].cpu().numpy()
+    i32 = lambda off, n: ws[off:off + 4 * n].view(np.int32).copy()
+    n_q = attn.shape[0]
+    return {
+        "layout": lay,
+        "row_lo": i32(lay.off_row_lo, n_q), "row_hi": i32(lay.off_row_hi, n_q),
+        "group": i32(lay.off_group, 4 * lay.n_groups).reshape(-1, 4),
+        "fwd_cost": i32(lay.off_fwd_cost, lay.n_fwd_tiles), "fwd_order": i32(lay.off_fwd_order, lay.n_fwd_tiles),
+        "fwd_prefix": ws[lay.off_fwd_prefix:lay.off_fwd_prefix + 8 * (lay.n_fwd_tiles + 1)].view(np.int64).copy(),
+        "tile_short": i32(lay.off_tile_short, lay.n_fwd_tiles),
+        "key_range": i32(lay.off_key_range, 2 * lay.n_key_tiles).reshape(-1, 2),
+        "key_ways": i32(lay.off_key_ways, lay.n_key_tiles), "key_order": i32(lay.off_key_order, lay.n_key_tiles),
+        "key_item_base": i32(lay.off_key_item_base, lay.n_key_tiles + 1),
+    }
+
+
+def plan_report(attn: "Attention", name: str = "") -> str:
+    """A few lines of text about the schedule in `attn`'s workspace: what the work items cost and how they are
+    spread (for looking at a schedule by eye; bench.py prints it when WLB_TRACE=1)."""
+    t = plan_tables(attn)
+    lay = t["layout"]
+    n_q, t_kv, n_docs, hq, hkv, d = attn.shape[:6]
+    cost = t["fwd_cost"][t["fwd_order"]].astype(np.int64)
+    per = np.diff(t["fwd_prefix"])
+    lines = [f"plan {name}: n_q {n_q} t_kv {t_kv} docs {n_docs} heads {hq}/{hkv} D {d}: "
+             f"{lay.n_fwd_tiles} query tiles ({int(t['tile_short'].sum())} short-hull), {lay.n_key_tiles} key tiles, "
+             f"{'gang' if lay.uses_gangs else 'item'} schedule for forward and dQ"]
+    q = lambda a: "min %d  median %d  max %d  sum %d" % (a.min(), np.median(a), a.max(), a.sum()) if len(a) else "none"
+    lines.append(f"  query tile cost (64-key tiles visited, heaviest first): {q(cost)}; first ten: {cost[:10].tolist()}")
+    if lay.uses_gangs:
+        w = wlb_attn_get_gang_weights(0).astype(np.int64).reshape(2, 8)
+        ng = lay.row_gangs
+        gw = np.array([w[0 if g < ng // 2 else 1][g % 8] for g in range(ng)])
+        cum = np.concatenate([[0], np.cumsum(gw)])
+        total = int(t["fwd_prefix"][-1]) * hkv
+        begin = total * cum // cum[-1]
+        share = np.diff(begin)
+        lines.append(f"  forward work line: {total} units (tile cost + fixed part, x KV heads) over {ng} gangs of {hq // hkv} "
+                     f"workgroups: share {q(share)}")
+    else:
+        lines.append(f"  forward / dQ items: {lay.n_fwd_tiles * hq} (tile, head), cost with fixed part {q(per)}")
+    kr = t["key_range"]
+    stages = (kr[:, 1] - kr[:, 0]).astype(np.int64) * (hq // hkv) // np.maximum(t["key_ways"], 1)
+    lines.append(f"  dK/dV items: {int(t['key_item_base'][-1])} (key tile, KV head, head part); tiles split "
+                 f"{dict(zip(*[x.tolist() for x in np.unique(t['key_ways'], return_counts=True)]))} ways; stages per item {q(stages)}")
+    return "\n".join(lines)
+
+
 def wlb_attn_get_gang_weights(kernel: int) -> np.ndarray:
     """The 16 weights in force for the forward (0) or dQ (1) gang kernel: [half of the launch][XCD]."""
     out = np.zeros(16, dtype=np.int32)

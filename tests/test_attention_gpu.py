@@ -179,6 +179,26 @@ def test_gang_weights_calibrated_from_the_clocks_keep_the_result():
     assert all(np.array_equal(B.wlb_attn_get_gang_weights(k), default[k]) for k in (0, 1))
 
 
+def test_plan_tables_and_report_describe_the_schedule():
+    """binding.plan_tables / plan_report: the host view of the schedule holds the row intervals of the mask's
+    definition (document start up to the row itself), orders and running sums that fit together, and the
+    text report names the shape and the counts."""
+    docs = [700, 3, 1500, 64, 64, 9]
+    c = _small(91, docs, 4, 2, 128)
+    c.attn.plan()
+    t = B.plan_tables(c.attn)
+    cu = _cu(docs)
+    pos = np.arange(sum(docs))
+    start = cu[np.searchsorted(cu, pos, side="right") - 1]
+    assert np.array_equal(t["row_lo"], start) and np.array_equal(t["row_hi"], pos + 1)
+    lay = t["layout"]
+    assert sorted(t["fwd_order"].tolist()) == list(range(lay.n_fwd_tiles))
+    assert t["fwd_prefix"][0] == 0 and (np.diff(t["fwd_prefix"]) > 0).all()
+    assert int(t["key_item_base"][-1]) == int((t["key_ways"] * 2).sum())
+    text = B.plan_report(c.attn, "case")
+    assert f"n_q {sum(docs)}" in text and f"{lay.n_fwd_tiles} query tiles" in text and "dK/dV items" in text
+
+
 def test_gang_schedule_on_one_row():
     """Degenerate work lines: a single query row, and fewer units of work than gangs."""
     for docs in ([1], [5, 1, 2]):
