@@ -598,6 +598,9 @@ __global__ void __launch_bounds__(256) dq_merge_kernel(const BwdParams p) {
     const int h = cut.hk * s.G + member;
     auto part = [&](int slot) { return p.row_partial + ((size_t)slot * s.G + member) * PF; };
     const float* first = part(cut.first_slot());
+    constexpr int CAP = 32;
+    __shared__ int s_slots[CAP], s_count;
+    const int n_later = gather_later_parts<CAP>(cut, s_slots, &s_count);
     constexpr int PER = BM * V4 / kMergeSplit;
     for (int e = quarter * PER + threadIdx.x; e < (quarter + 1) * PER; e += 256) {
         const int rl = e / V4, d4 = e % V4;
@@ -605,7 +608,11 @@ __global__ void __launch_bounds__(256) dq_merge_kernel(const BwdParams p) {
         if (row >= p.n_q) continue;
         const size_t at = (size_t)rl * D + d4 * 4;
         f32x4 sum = *reinterpret_cast<const f32x4*>(first + at);
-        cut.later_parts([&](int slot) { sum += *reinterpret_cast<const f32x4*>(part(slot) + at); });
+        if (n_later <= CAP) {
+            for (int i = 0; i < n_later; ++i) sum += *reinterpret_cast<const f32x4*>(part(s_slots[i]) + at);
+        } else {
+            cut.later_parts([&](int slot) { sum += *reinterpret_cast<const f32x4*>(part(slot) + at); });
+        }
         const bool real = p.row_hi[row] > 0;
         *reinterpret_cast<bf16x4*>(p.dq + ((size_t)row * p.hq + h) * D + d4 * 4) =
             real ? pack4(sum[0] * p.scale, sum[1] * p.scale, sum[2] * p.scale, sum[3] * p.scale) : pack4(0.f, 0.f, 0.f, 0.f);

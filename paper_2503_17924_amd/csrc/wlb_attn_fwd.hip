@@ -586,7 +586,16 @@ __global__ void __launch_bounds__(256) fwd_merge_kernel(const FwdParams p) {
     const int h = cut.hk * s.G + member;
     auto part = [&](int slot) { return p.partial + ((size_t)slot * s.G + member) * PF; };
     const float* first = part(cut.first_slot());
-    auto later_parts = [&](auto f) __attribute__((always_inline)) { cut.later_parts([&](int slot) { f(part(slot)); }); };
+    constexpr int CAP = 32;
+    __shared__ int s_slots[CAP], s_count;
+    const int n_later = gather_later_parts<CAP>(cut, s_slots, &s_count);
+    auto later_parts = [&](auto f) __attribute__((always_inline)) {
+        if (n_later <= CAP) {
+            for (int i = 0; i < n_later; ++i) f(part(s_slots[i]));
+        } else {
+            cut.later_parts([&](int slot) { f(part(slot)); });
+        }
+    };
     constexpr int PER = BM * V4 / kMergeSplit;
     for (int e = quarter * PER + threadIdx.x; e < (quarter + 1) * PER; e += 256) {
         const int rl = e / V4, d4 = e % V4;

@@ -205,6 +205,24 @@ struct RowCut {
     }
 };
 
+// The slot indices of a cut tile's later parts, found once per workgroup (each step of RowCut::later_parts
+// costs two 64-bit divisions, and the merge kernels need the list for every element they combine): thread 0
+// walks them and leaves up to CAP of them in shared memory.  Returns their number; above CAP the caller
+// falls back to RowCut::later_parts.  Every thread of the workgroup must call it.
+template <int CAP>
+__device__ __forceinline__ int gather_later_parts(const RowCut& cut, int* s_slots, int* s_count) {
+    if (threadIdx.x == 0) {
+        int n = 0;
+        cut.later_parts([&](int slot) {
+            if (n < CAP) s_slots[n] = slot;
+            ++n;
+        });
+        *s_count = n;
+    }
+    __syncthreads();
+    return *s_count;
+}
+
 // XOR swizzle of the 16-byte chunks of an unpadded row-major LDS tile whose rows hold CPR
 // chunks: logical chunk cc of row r is stored at chunk swz(r, cc).  It makes both access patterns
 // of the kernels bank-conflict free: 16 rows x one chunk (b128 MFMA operand reads) and 4 rows x 4
