@@ -55,13 +55,17 @@ template <int D>
 __global__ void __launch_bounds__(256) delta_kernel(const BwdParams p) {
     constexpr int LPR = D / 8;                       // lanes per (row, head)
     const size_t total = (size_t)p.n_q * p.hq;
-    // a fixed number of workgroups walks the (row, head) pairs: rows of short-hull tiles, whose delta and
-    // LSE copy come from the short-hull dQ units, then cost a table lookup instead of a workgroup
-    for (size_t base = (size_t)blockIdx.x * 256; base < total * LPR; base += (size_t)gridDim.x * 256) {
-        const size_t idx = base + threadIdx.x;
+    // gridDim.x / n_tiles workgroups share the (row, head) pairs of a query tile.  A short-hull tile, whose delta
+    // and LSE copy come from the short-hull dQ units, costs its workgroups one table lookup.
+    const int split = (int)gridDim.x / p.n_tiles;
+    const int tile = (int)blockIdx.x / split, part = (int)blockIdx.x % split;
+    if (tile >= p.n_tiles || (p.delta_skips_short && ld_const(p.tile_short + tile))) return;
+    const size_t first = (size_t)tile * kFwdTileRows * p.hq * LPR, lanes = (size_t)kFwdTileRows * p.hq * LPR;
+    for (size_t off = (size_t)part * 256; off < lanes; off += (size_t)split * 256) {
+        const size_t idx = first + off + threadIdx.x;
         const size_t rh = idx / LPR;                 // row * hq + head
         const int c = (int)(idx % LPR);
-        const bool mine = rh < total && !(p.delta_skips_short && p.tile_short[(rh / p.hq) / kFwdTileRows]);
+        const bool mine = rh < total;
         float acc = 0.f;
         if (mine) {
             const bf16x8 a = *reinterpret_cast<const bf16x8*>(p.d_o + rh * D + c * 8);
@@ -1105,8 +1109,10 @@ wlb_status launch_bwd(const wlb_attn_desc& d, const wlb_plan_layout& L, const vo
     p.scale = d.scale;
     p.scale_log2e = d.scale * 1.4426950408889634f;
 
-    const size_t n_lanes = (size_t)d.n_q * d.hq * (d.head_dim / 8);
-    const unsigned grid_delta = (unsigned)std::min<size_t>((n_lanes + 255) / 256, 8 * (size_t)compute_units());
+    // workgroups per query tile in the delta pass: enough to fill the GPU, at most one per 256 lanes of the tile
+    const size_t tile_iters = (size_t)kFwdTileRows * d.hq * (d.head_dim / 8) / 256;
+    const size_t delta_split = std::max<size_t>(1, std::min(tile_iters, (8 * (size_t)compute_units() + L.n_fwd_tiles - 1) / L.n_fwd_tiles));
+    const unsigned grid_delta = (unsigned)(delta_split * L.n_fwd_tiles);
     const unsigned grid_dq = (unsigned)L.row_gangs * (unsigned)(d.hq / d.hkv);
     const unsigned grid_dq_items = (unsigned)((L.n_fwd_tiles + 7) / 8) * 8u * (unsigned)d.hq;
     const bool gangs = use_row_gangs(d, L);
