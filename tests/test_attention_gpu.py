@@ -90,6 +90,26 @@ def test_forward_rows_in_arbitrary_order():
     Case(tens, q_idx, _cu(docs), 2, 2, 128, w.scale).check_fwd()
 
 
+@pytest.mark.parametrize("flag", [B.ATTN_SCHEDULE_GANGS, B.ATTN_SCHEDULE_ITEMS])
+def test_wavefront_with_rows_of_two_chunks_and_three_documents(flag):
+    """32 consecutive rows (one wavefront of the forward and dQ kernels) that hold rows of an early and of a late
+    chunk of one long document, rows of a second document and a row of a third, padding in between: the kernels
+    cross the keys between the chunks, and the other documents' keys, with whole lanes switched off, in several
+    ranges.  Every output element against the oracle, forward and backward."""
+    docs = [2000, 700, 300, 77]
+    cu = _cu(docs)
+    rows = ([int(cu[0]) + i for i in range(0, 9)] + [-1, -1] + [int(cu[0]) + 1900 + i for i in range(7)]
+            + [int(cu[1]) + 130 + 3 * i for i in range(8)] + [-1] + [int(cu[2]) + 299] + [int(cu[1]) + 699, int(cu[1]), -1, int(cu[0]) + 1999])
+    assert len(rows) == 32
+    # a second wavefront of ordinary rows and a third that starts in the last document
+    rows += [int(cu[0]) + 640 + i for i in range(32)] + [int(cu[3]) + i for i in range(20)]
+    w, tens = wl.small_case(97, docs, 8, 2, 128)
+    c = Case(tens, np.asarray(rows, dtype=np.int32), cu, 8, 2, 128, w.scale)
+    c.flags = flag
+    c.check_fwd(" mixed wavefront")
+    c.check_bwd(" mixed wavefront")
+
+
 def test_forward_config0_both_ranks():
     w = wl.config(0)
     tens = w.tensors(names=("q", "k", "v"))
