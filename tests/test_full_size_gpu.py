@@ -19,13 +19,15 @@ pytestmark = pytest.mark.gpu
 
 
 def _rows_sample(q_idx, cu, n, rng):
-    """Real local rows: the first and last rows of every document present plus random ones."""
+    """Real local rows: the first and last rows of every document present, the rows on both sides of the middle of
+    its local rows (under per-document sharding the boundary between the early and the late chunk, which share a
+    wavefront), plus random ones."""
     real = np.nonzero(q_idx >= 0)[0]
     doc = np.searchsorted(cu, q_idx[real], side="right") - 1
     picks = []
     for d in np.unique(doc):
         r = real[doc == d]
-        picks += [r[0], r[-1], r[len(r) // 2]]
+        picks += [r[0], r[-1], r[len(r) // 2], r[max(len(r) // 2 - 1, 0)]]
     picks += rng.choice(real, size=min(n, len(real)), replace=False).tolist()
     return np.unique(np.asarray(picks))
 
