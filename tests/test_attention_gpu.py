@@ -189,7 +189,7 @@ def test_gang_weights_calibrated_from_the_clocks_keep_the_result():
             f = np.asarray(factors[name])
             assert (f >= 0.8).all() and (f <= 1.25).all()
             want = default[k].astype(np.float64).reshape(2, 8) * f[None, :] * 10.0
-            assert np.abs(got - want).max() <= 0.51
+            assert np.abs(got - want).max() <= 1.0      # rounding to integers plus the factors' four decimals
         c.check_fwd(" calibrated weights")
         c.check_bwd(" calibrated weights")
         assert B.calibrate_gang_weights([c.attn], launch) is None, "without the flag this problem does not use gangs"
