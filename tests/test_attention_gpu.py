@@ -110,6 +110,47 @@ def test_wavefront_with_rows_of_two_chunks_and_three_documents(flag):
     c.check_bwd(" mixed wavefront")
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_shapes_match_oracle(seed):
+    """A seeded sweep over valid small inputs: document mixes (tiny, mixed, one long plus tiny, medium), head counts
+    with groups of 1 to 8 query heads per KV head, both head dimensions, CP 1 to 4 with padded and padding-free maps,
+    every schedule flag, and for some cases shuffled rows with extra padding.  Forward and backward, every element."""
+    rng = np.random.default_rng(seed)
+    for it in range(25):
+        n_docs = int(rng.integers(1, 12))
+        kind = int(rng.integers(0, 4))
+        if kind == 0:
+            docs = rng.integers(1, 70, size=n_docs * 6).tolist()
+        elif kind == 1:
+            docs = rng.integers(1, 1500, size=n_docs).tolist()
+        elif kind == 2:
+            docs = [int(rng.integers(1500, 4000))] + rng.integers(1, 100, size=n_docs).tolist()
+        else:
+            docs = rng.integers(100, 700, size=n_docs).tolist()
+        if sum(docs) > 6000:
+            docs = docs[:max(1, len(docs) // 2)]
+        hkv = int(rng.choice([1, 2, 3, 4]))
+        hq = hkv * int(rng.choice([1, 2, 3, 4, 5, 7, 8]))
+        if hq > 16:
+            hq, hkv = 8, 2
+        d = int(rng.choice([64, 128]))
+        cp = int(rng.choice([1, 1, 2, 3, 4]))
+        rank = int(rng.integers(0, cp))
+        mode = int(rng.choice([osh.PER_DOC_PADDED, osh.PER_DOC_NOPAD])) if cp > 1 else osh.PER_DOC_PADDED
+        flag = int(rng.choice([0, B.ATTN_SCHEDULE_GANGS, B.ATTN_SCHEDULE_ITEMS, B.ATTN_SCHEDULE_ITEMS | B.ATTN_NO_SHORT_PATH]))
+        tag = f" seed {seed} case {it}: docs {docs} hq {hq} hkv {hkv} d {d} cp {cp} rank {rank} mode {mode} flag {flag}"
+        w, tens = wl.small_case(1000 * seed + it, docs, hq, hkv, d)
+        sh = osh.shard(docs, cp, rank, mode)
+        q_idx = sh["q_idx"].copy()
+        if rng.random() < 0.3 and len(q_idx) > 4:
+            q_idx = rng.permutation(q_idx)
+            q_idx[rng.integers(0, len(q_idx), size=max(1, len(q_idx) // 10))] = -1
+        c = Case(tens, q_idx, sh["cu_seqlens_k"], hq, hkv, d, w.scale)
+        c.flags = flag
+        c.check_fwd(tag)
+        c.check_bwd(tag)
+
+
 def test_forward_config0_both_ranks():
     w = wl.config(0)
     tens = w.tensors(names=("q", "k", "v"))
