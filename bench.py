@@ -89,7 +89,7 @@ class RankState:
         self.n_q = len(qi)
         self.n_real = int((qi >= 0).sum())
         self.q_idx_host = torch.from_numpy(qi.copy()).pin_memory()
-        self.attn = B.Attention(qi, sh["cu_seqlens_k"], total_tokens, hq, hkv, d, scale, device)
+        self.attn = B.Attention(qi, sh["cu_seqlens_k"], total_tokens, hq, hkv, d, scale, device, visible_pairs=self.pairs)
         if cp == 1:
             self.q, self.do = full["q"], full["do"]
         else:

@@ -180,6 +180,11 @@ typedef struct {
     int32_t head_dim;  /* 64 or 128                                                   */
     float   scale;     /* softmax scale, finite and > 0                               */
     int32_t flags;     /* WLB_ATTN_* bits                                             */
+    /* In-document causal (row, key) pairs these rows see, per head -- wlb_shard's useful_pairs for this rank -- or
+     * 0 if not known.  It never changes a result: the host only uses it to choose between the two work schedules
+     * of the forward and dQ kernels from the real amount of work; without it the choice rests on the mean document
+     * length (the host does not see the mask), which misjudges a long document among many tiny ones. */
+    int64_t visible_pairs;
 } wlb_attn_desc;
 
 enum {

@@ -45,7 +45,8 @@ class WlbError(RuntimeError):
 
 class AttnDesc(C.Structure):
     _fields_ = [("n_q", C.c_int32), ("t_kv", C.c_int32), ("n_docs", C.c_int32), ("hq", C.c_int32),
-                ("hkv", C.c_int32), ("head_dim", C.c_int32), ("scale", C.c_float), ("flags", C.c_int32)]
+                ("hkv", C.c_int32), ("head_dim", C.c_int32), ("scale", C.c_float), ("flags", C.c_int32),
+                ("visible_pairs", C.c_int64)]
 
 
 class PlanLayout(C.Structure):
@@ -274,8 +275,9 @@ def wlb_shard(doc_len, cp: int, rank: int, mode: int):
 
 
 # ----------------------------------------------------------------------------- device calls
-def _desc(n_q, t_kv, n_docs, hq, hkv, head_dim, scale, flags=0):
-    return AttnDesc(int(n_q), int(t_kv), int(n_docs), int(hq), int(hkv), int(head_dim), float(scale), int(flags))
+def _desc(n_q, t_kv, n_docs, hq, hkv, head_dim, scale, flags=0, visible_pairs=0):
+    return AttnDesc(int(n_q), int(t_kv), int(n_docs), int(hq), int(hkv), int(head_dim), float(scale), int(flags),
+                    int(visible_pairs))
 
 
 def wlb_attn_workspace_size(desc: AttnDesc):
@@ -344,7 +346,7 @@ def wlb_attn_bwd(desc, q, k, v, o, lse, d_o, q_idx, cu_seqlens_k, dq, dk, dv, wo
 class Attention:
     """Owns the output tensors and workspace for one (shape, mask); all arithmetic is in libwlb."""
 
-    def __init__(self, q_idx, cu_seqlens_k, t_kv, hq, hkv, head_dim, scale, device="cuda:0"):
+    def __init__(self, q_idx, cu_seqlens_k, t_kv, hq, hkv, head_dim, scale, device="cuda:0", visible_pairs=0):
         import torch
         self.torch = torch
         self.device = torch.device(device)
@@ -352,11 +354,15 @@ class Attention:
         self.cu_k = torch.as_tensor(np.ascontiguousarray(cu_seqlens_k, dtype=np.int32)).to(self.device)
         self.n_q = int(self.q_idx.numel())
         self.shape = (self.n_q, int(t_kv), int(self.cu_k.numel()) - 1, hq, hkv, head_dim, scale)
-        self.desc = _desc(*self.shape)
-        self.desc_reuse = _desc(*self.shape, flags=ATTN_REUSE_PLAN)
+        self.visible_pairs = int(visible_pairs)     # wlb_shard's useful_pairs, if the caller has it (schedule choice only)
+        self.desc = self.make_desc(0)
+        self.desc_reuse = self.make_desc(ATTN_REUSE_PLAN)
         _, bwd_bytes = wlb_attn_workspace_size(self.desc)
         self.workspace = torch.empty(bwd_bytes, dtype=torch.uint8, device=self.device)
         self.planned = False
+
+    def make_desc(self, flags):
+        return _desc(*self.shape, flags=flags, visible_pairs=self.visible_pairs)
 
     def plan(self):
         wlb_attn_plan(self.desc, self.q_idx, self.cu_k, self.workspace)
@@ -371,7 +377,7 @@ class Attention:
             lse = torch.empty((hq, n_q), dtype=torch.float32, device=self.device)
         desc = self.desc_reuse if self.planned else self.desc
         if extra_flags:
-            desc = _desc(*self.shape, flags=desc.flags | extra_flags)
+            desc = self.make_desc(desc.flags | extra_flags)
         wlb_attn_fwd(desc, q, k, v, self.q_idx, self.cu_k, o, lse, self.workspace)
         self.planned = True
         return o, lse
@@ -386,7 +392,7 @@ class Attention:
             dv = torch.empty_like(v)
         desc = self.desc_reuse if self.planned else self.desc
         if extra_flags:
-            desc = _desc(*self.shape, flags=desc.flags | extra_flags)
+            desc = self.make_desc(desc.flags | extra_flags)
         wlb_attn_bwd(desc, q, k, v, o, lse, d_o, self.q_idx, self.cu_k, dq, dk, dv, self.workspace)
         self.planned = True
         return dq, dk, dv
@@ -486,7 +492,7 @@ def calibrate_gang_weights(attns, launch, rounds: int = 3, extra_flags: int = 0)
     hold for the process (wlb_attn_set_gang_weights(k, None) restores the defaults).  Returns
     {"fwd": [8 factors], "dq": [8 factors]} (relative speeds, mean 1), or None if no problem uses gangs."""
     import torch
-    use = [a for a in attns if wlb_attn_plan_layout(_desc(*a.shape, flags=a.desc.flags | extra_flags)).uses_gangs]
+    use = [a for a in attns if wlb_attn_plan_layout(a.make_desc(a.desc.flags | extra_flags)).uses_gangs]
     if not use:
         return None
     factor = np.ones((2, 8))

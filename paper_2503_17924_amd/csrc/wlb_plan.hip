@@ -24,6 +24,7 @@ wlb_status check_desc(const wlb_attn_desc* d) {
         return fail(WLB_ERR_INVALID_ARG, "attention: n_q=%d t_kv=%d n_docs=%d hq=%d hkv=%d", d->n_q, d->t_kv,
                     d->n_docs, d->hq, d->hkv);
     if (d->hq % d->hkv != 0) return fail(WLB_ERR_INVALID_ARG, "attention: hq=%d not a multiple of hkv=%d", d->hq, d->hkv);
+    if (d->visible_pairs < 0) return fail(WLB_ERR_INVALID_ARG, "attention: visible_pairs=%lld", (long long)d->visible_pairs);
     if ((d->flags & WLB_ATTN_SCHEDULE_GANGS) && (d->flags & WLB_ATTN_SCHEDULE_ITEMS))
         return fail(WLB_ERR_INVALID_ARG, "attention: both schedule flags set");
     if (!(d->scale > 0.0f) || !std::isfinite(d->scale)) return fail(WLB_ERR_INVALID_ARG, "attention: scale must be finite and > 0");
@@ -61,9 +62,12 @@ bool use_row_gangs(const wlb_attn_desc& d, const wlb_plan_layout& L) {
     if (d.flags & WLB_ATTN_SCHEDULE_ITEMS) return false;
     const long long items = (long long)L.n_fwd_tiles * d.hq, slots = 2LL * compute_units();
     if (items >= (long long)kRowGangMaxItemsPerSlot * slots) return false;
-    // and only when a slot's share is worth cutting tiles for: estimated from the mean document length
-    // (a tile sees about half its document: length / 128 key tiles), since the host does not see the mask
-    const long long per_item = d.t_kv / d.n_docs / (2 * 64) + kRowItemOverhead;
+    // and only when a slot's share is worth cutting tiles for.  The work line's length in key tiles per item:
+    // from the caller's pair count when it gave one (a tile of 128 rows x 64 keys holds 8192 pairs), else
+    // estimated from the mean document length (a tile sees about half its document: length / 128 key tiles),
+    // since the host does not see the mask
+    const long long per_item = (d.visible_pairs > 0 ? d.visible_pairs / ((long long)L.n_fwd_tiles * kFwdTileRows * 64)
+                                                    : (long long)(d.t_kv / d.n_docs / (2 * 64))) + kRowItemOverhead;
     return items * per_item >= (long long)kRowGangMinUnitsPerSlot * slots;
 }
 

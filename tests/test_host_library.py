@@ -114,6 +114,28 @@ def test_pack_errors_and_limits():
     assert B.wlb_pack(np.asarray([11, 5], dtype=np.int32), 2, 10, 1, 0)[0].tolist() == [-1, 0]
 
 
+def test_schedule_choice_uses_the_pair_count_when_given():
+    """One rank of a 128K micro-batch made of one long document among 500 tiny ones: 128 query tiles x 8 heads are
+    few items per workgroup slot, and nearly all work sits in the long document's tiles.  From the mean document
+    length alone the host takes the work for small and picks one workgroup per item; with the rank's pair count
+    (wlb_shard's useful_pairs) in the descriptor it picks the gang schedule, as it does for a few long documents.
+    With many items per slot it is one workgroup per item either way; a negative count is an error."""
+    docs = np.asarray([100000] + [62] * 500 + [72], dtype=np.int32)
+    assert docs.sum() == 131072
+    sh = B.wlb_shard(docs, 8, 3, B.SHARD_PER_DOC_PADDED)
+    n_q, pairs = len(sh["q_idx"]), sh["useful_pairs"]
+    assert pairs > 5e8
+    blind = B.wlb_attn_plan_layout(B._desc(n_q, 131072, len(docs), 8, 1, 128, 0.1))
+    told = B.wlb_attn_plan_layout(B._desc(n_q, 131072, len(docs), 8, 1, 128, 0.1, visible_pairs=pairs))
+    assert (blind.uses_gangs, told.uses_gangs) == (0, 1)
+    assert B.wlb_attn_plan_layout(B._desc(n_q, 131072, 16, 8, 1, 128, 0.1)).uses_gangs == 1
+    assert B.wlb_attn_plan_layout(B._desc(131072, 131072, len(docs), 16, 2, 128, 0.1, visible_pairs=8 * pairs)).uses_gangs == 0
+    assert B.wlb_attn_plan_layout(B._desc(n_q, 131072, len(docs), 8, 1, 128, 0.1, flags=B.ATTN_SCHEDULE_ITEMS,
+                                          visible_pairs=pairs)).uses_gangs == 0
+    with pytest.raises(B.WlbError):
+        B.wlb_attn_plan_layout(B._desc(n_q, 131072, len(docs), 8, 1, 128, 0.1, visible_pairs=-1))
+
+
 def test_attention_argument_checks_need_no_gpu():
     d = B._desc(128, 128, 1, 4, 3, 128, 0.1)
     with pytest.raises(B.WlbError) as e:
